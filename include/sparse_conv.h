@@ -1,0 +1,140 @@
+/*
+ * sparse_conv.h - C ABI of the MI355X (gfx950) direct sparse convolution library.
+ *
+ * Direct sparse convolution (Pietron & Zurek, arXiv 2011.06295, sections 7 and
+ * 8): the weights of a convolution layer that survived unstructured pruning
+ * are stored per output channel in CSR and multiplied straight against the
+ * dense NCHW input, with no im2col lowering.  The result is the plain
+ * convolution of section 3, eq. 1, evaluated over the kept weights only.
+ *
+ * Conventions shared by all entry points
+ *   - every function returns an int status (SC_OK or a negative SC_E* code),
+ *     never throws and never aborts; on error the outputs are left untouched;
+ *   - HOST pointers are ordinary process memory, DEVICE pointers are HIP
+ *     device memory of the current device (for instance tensor.data_ptr() of a
+ *     PyTorch-ROCm tensor); the library never takes ownership of either;
+ *   - all arrays are dense, contiguous, row-major in the index order written;
+ *   - the handle is not thread-safe against concurrent calls on itself.
+ */
+#ifndef SPARSE_CONV_H
+#define SPARSE_CONV_H
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct sparse_conv_s* sparse_conv_t; /* opaque layer handle */
+
+enum {
+    SC_OK = 0,
+    SC_EINVAL = -1,       /* null pointer, non-positive size, stride < 1, pad < 0, filter larger than padded input, unknown dtype/flag */
+    SC_EUNSUPPORTED = -2, /* valid request this build cannot run (e.g. a tile that cannot fit the LDS, no gfx950 device) */
+    SC_ENOMEM = -3,       /* host or device allocation failed */
+    SC_EHIP = -4          /* a HIP runtime call failed; sparse_conv_last_hip_error() has the code */
+};
+
+/* Storage type of weights, input and output.  Products and sums are always
+ * formed in fp32 (section 8: the half path converts the value array and the
+ * input to half; accumulation width is this library's choice). */
+enum { SC_F32 = 0, SC_F16 = 1 };
+
+/* Section 7: pad every CSR row with explicit zeros up to the non-zero count of
+ * the fullest row, so all output channels have one unified count. */
+enum { SC_FLAG_UNIFY_NNZ = 1u };
+
+/*
+ * sparse_conv_create - build the CSR form of one pruned layer (section 7).
+ *   out      receives the handle.
+ *   dense_w  HOST, fp32 [K][C][R][S]: the dense filter tensor of section 3.
+ *   mask     HOST, uint8 [K][C][R][S]: non-zero = the weight survives pruning
+ *            (section 5, eq. 4: w <- w * mask).  The mask, not the value,
+ *            decides what is stored; kept values are copied bit for bit
+ *            (SC_F16: converted once to IEEE binary16, round-to-nearest-even).
+ *   K,C,R,S  output channels, input channels, filter height, filter width (> 0,
+ *            C*R*S and the total stored count below 2^31).
+ *   dtype    SC_F32 or SC_F16.
+ *   flags    0 or SC_FLAG_UNIFY_NNZ.
+ * CSR layout: row k = output channel k; column = (c*R + r)*S + s; entries of a
+ * row in ascending column order; 32-bit rowptr[K+1] and colidx[nnz].
+ * With SC_FLAG_UNIFY_NNZ a short row is extended to the count of the fullest
+ * row: scanning columns upwards, a dropped column directly right of a stored
+ * one (possibly just added) is stored with value +0.0 until the row is full;
+ * if it is still short the lowest dropped columns are added.
+ * Both input arrays are copied; the caller may free them on return.  No GPU is
+ * needed for this call: device copies are made by the first forward call.
+ */
+int sparse_conv_create(sparse_conv_t* out, const float* dense_w, const unsigned char* mask,
+                       int K, int C, int R, int S, int dtype, unsigned flags);
+
+/*
+ * sparse_conv_output_shape - section 3: E = (H + 2*pad - R)/stride + 1 and
+ * F = (W + 2*pad - S)/stride + 1, with floor division.  SC_EINVAL if the
+ * padded input is smaller than the filter.
+ */
+int sparse_conv_output_shape(sparse_conv_t h, int H, int W, int stride, int pad, int* E, int* F);
+
+/*
+ * sparse_conv_forward - direct sparse convolution (section 8) of a batch.
+ *   input   DEVICE, [N][C][H][W] of the handle's dtype (fp32 or binary16).
+ *   output  DEVICE, [N][K][E][F] of the same dtype; every element is written
+ *           (channels with no stored weight are written as zeros).  Must not
+ *           overlap input.
+ *   N,H,W   batch size (>= 0; 0 is a no-op) and input height/width (> 0).
+ *   stride  >= 1, the same in both directions.   pad >= 0, zero padding.
+ *   stream  a hipStream_t passed as void*; NULL is the default stream.
+ * Asynchronous: kernels are enqueued on the stream and the call returns
+ * without synchronising.  The first call for a new (N,H,W,stride,pad) builds
+ * and uploads a per-geometry plan (one synchronous allocation + copy);
+ * further calls with the same geometry allocate nothing.
+ */
+int sparse_conv_forward(sparse_conv_t h, const void* input, void* output,
+                        int N, int H, int W, int stride, int pad, void* stream);
+
+/*
+ * sparse_conv_get_csr - expose the CSR arrays built by create (section 7).
+ * All pointers are HOST memory owned by the handle, valid until destroy; any
+ * of the out-pointers may be NULL.  values points to float (SC_F32) or to
+ * 16-bit binary16 patterns (SC_F16).
+ */
+int sparse_conv_get_csr(sparse_conv_t h, int* K, long long* nnz,
+                        const int** rowptr, const int** colidx, const void** values);
+
+/*
+ * sparse_conv_set_launch - override the per-layer launch configuration, this
+ * library's counterpart of the per-layer thread-block count the paper tunes
+ * (section 8, subBatchSize; section 9).  params[0..nparams) are, in order:
+ *   [0] V   images interleaved per LDS element (1, 2, 4 or 8; 0 = automatic)
+ *   [1] G   image groups (of V images) per workgroup tile
+ *   [2] B   output rows per tile (0 = all rows)
+ *   [3] Cc  input channels staged per LDS pass
+ *   [4] WP  wavefronts across output positions
+ *   [5] WK  wavefronts across output channels
+ *   [6] KW  output channels accumulated per wavefront (1, 2, 4, 8 or 16)
+ *   [7] LDS budget in bytes per workgroup (0 = default)
+ * Missing trailing entries and zeros mean "automatic".  nparams = 0 restores
+ * the automatic choice.  Cached plans are discarded.  SC_EINVAL for values the
+ * kernels cannot run; a configuration that cannot fit is reported by forward.
+ */
+int sparse_conv_set_launch(sparse_conv_t h, const int* params, int nparams);
+
+/* The launch configuration chosen for a geometry, in the order of
+ * sparse_conv_set_launch, followed by [8] workgroups launched, [9] LDS bytes
+ * per workgroup, [10] threads per workgroup, [11] stored plan entries
+ * (including batch padding).  Builds the plan's host side if needed; needs no
+ * GPU.  params must have room for 12 ints. */
+int sparse_conv_get_launch(sparse_conv_t h, int N, int H, int W, int stride, int pad, int* params);
+
+/* HIP error code of the last failing runtime call made through this handle (0 if none). */
+int sparse_conv_last_hip_error(sparse_conv_t h);
+
+/* Static description of a status code. */
+const char* sparse_conv_strerror(int code);
+
+/* Release the handle, its host arrays and its device buffers.  NULL is a no-op.
+ * The caller must make sure no forward call on the handle is still running. */
+void sparse_conv_destroy(sparse_conv_t h);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPARSE_CONV_H */

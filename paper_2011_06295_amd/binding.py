@@ -1,0 +1,187 @@
+"""Thin ctypes binding of libsparseconv.so (include/sparse_conv.h).
+
+Argument marshalling only: every step of direct sparse convolution (CSR
+encoding, per-geometry plan, LDS staging, gather-FMA, store) runs inside the
+library.  PyTorch appears only as the owner of device buffers and streams.
+There is no fallback: if the library is not built, importing fails loudly.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence, Tuple
+
+import numpy as np
+
+SC_OK, SC_EINVAL, SC_EUNSUPPORTED, SC_ENOMEM, SC_EHIP = 0, -1, -2, -3, -4
+SC_F32, SC_F16 = 0, 1
+SC_FLAG_UNIFY_NNZ = 1
+
+LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libsparseconv.so")
+
+EXPORTS = (
+    "sparse_conv_create", "sparse_conv_output_shape", "sparse_conv_forward",
+    "sparse_conv_get_csr", "sparse_conv_set_launch", "sparse_conv_get_launch",
+    "sparse_conv_last_hip_error", "sparse_conv_strerror", "sparse_conv_destroy",
+)
+
+
+class SparseConvError(RuntimeError):
+    def __init__(self, code: int, where: str, hip: int = 0):
+        self.code = code
+        self.hip = hip
+        msg = _lib.sparse_conv_strerror(code).decode() if _lib is not None else str(code)
+        super().__init__(f"{where}: {msg} (status {code}" + (f", hip error {hip})" if hip else ")"))
+
+
+def _load():
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_2011_06295_amd.build` "
+            "(there is no CPU fallback)")
+    lib = C.CDLL(LIB_PATH)
+    vp, ip = C.c_void_p, C.POINTER(C.c_int)
+    lib.sparse_conv_create.argtypes = [C.POINTER(vp), vp, vp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_uint]
+    lib.sparse_conv_output_shape.argtypes = [vp, C.c_int, C.c_int, C.c_int, C.c_int, ip, ip]
+    lib.sparse_conv_forward.argtypes = [vp, vp, vp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, vp]
+    lib.sparse_conv_get_csr.argtypes = [vp, ip, C.POINTER(C.c_longlong), C.POINTER(vp), C.POINTER(vp), C.POINTER(vp)]
+    lib.sparse_conv_set_launch.argtypes = [vp, ip, C.c_int]
+    lib.sparse_conv_get_launch.argtypes = [vp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, ip]
+    lib.sparse_conv_last_hip_error.argtypes = [vp]
+    lib.sparse_conv_strerror.argtypes = [C.c_int]
+    lib.sparse_conv_strerror.restype = C.c_char_p
+    lib.sparse_conv_destroy.argtypes = [vp]
+    lib.sparse_conv_destroy.restype = None
+    for name in EXPORTS:
+        if name not in ("sparse_conv_strerror", "sparse_conv_destroy"):
+            getattr(lib, name).restype = C.c_int
+    return lib
+
+
+_lib = None
+_lib = _load()
+
+
+def _check(rc: int, where: str, handle=None):
+    if rc != SC_OK:
+        hip = _lib.sparse_conv_last_hip_error(handle) if handle else 0
+        raise SparseConvError(rc, where, hip)
+
+
+# ---------------------------------------------------------------- same-name functions
+
+def sparse_conv_create(dense_w: np.ndarray, mask: np.ndarray, dtype: int = SC_F32, flags: int = 0) -> int:
+    """Handle for the layer with HOST fp32 weights [K][C][R][S] and uint8 mask of the same shape."""
+    w = np.ascontiguousarray(dense_w, dtype=np.float32)
+    m = np.ascontiguousarray(mask, dtype=np.uint8)
+    if w.ndim != 4 or m.shape != w.shape:
+        raise ValueError("dense_w and mask must both be [K][C][R][S]")
+    K, Cc, R, S = w.shape
+    h = C.c_void_p()
+    _check(_lib.sparse_conv_create(C.byref(h), w.ctypes.data, m.ctypes.data, K, Cc, R, S, dtype, flags),
+           "sparse_conv_create")
+    return h.value
+
+
+def sparse_conv_output_shape(handle: int, H: int, W: int, stride: int, pad: int) -> Tuple[int, int]:
+    e, f = C.c_int(), C.c_int()
+    _check(_lib.sparse_conv_output_shape(handle, H, W, stride, pad, C.byref(e), C.byref(f)),
+           "sparse_conv_output_shape", handle)
+    return e.value, f.value
+
+
+def sparse_conv_forward(handle: int, input_ptr: int, output_ptr: int, N: int, H: int, W: int,
+                        stride: int, pad: int, stream: int = 0) -> None:
+    """Enqueue the convolution of DEVICE input [N][C][H][W] into DEVICE output [N][K][E][F]."""
+    _check(_lib.sparse_conv_forward(handle, input_ptr, output_ptr, N, H, W, stride, pad, stream or None),
+           "sparse_conv_forward", handle)
+
+
+def sparse_conv_get_csr(handle: int, dtype: int):
+    """Copies of (rowptr int32, colidx int32, values float32|uint16 patterns)."""
+    K, nnz = C.c_int(), C.c_longlong()
+    rp, ci, va = C.c_void_p(), C.c_void_p(), C.c_void_p()
+    _check(_lib.sparse_conv_get_csr(handle, C.byref(K), C.byref(nnz), C.byref(rp), C.byref(ci), C.byref(va)),
+           "sparse_conv_get_csr", handle)
+    n = nnz.value
+
+    def arr(ptr, count, ctype, npdtype):
+        if count == 0 or not ptr.value:
+            return np.empty(0, dtype=npdtype)
+        return np.ctypeslib.as_array(C.cast(ptr, C.POINTER(ctype)), shape=(count,)).astype(npdtype, copy=True)
+
+    rowptr = arr(rp, K.value + 1, C.c_int, np.int32)
+    colidx = arr(ci, n, C.c_int, np.int32)
+    values = arr(va, n, C.c_uint16, np.uint16) if dtype == SC_F16 else arr(va, n, C.c_float, np.float32)
+    return rowptr, colidx, values
+
+
+def sparse_conv_set_launch(handle: int, params: Sequence[int]) -> None:
+    arr = (C.c_int * max(1, len(params)))(*params)
+    _check(_lib.sparse_conv_set_launch(handle, arr, len(params)), "sparse_conv_set_launch", handle)
+
+
+def sparse_conv_get_launch(handle: int, N: int, H: int, W: int, stride: int, pad: int) -> dict:
+    arr = (C.c_int * 12)()
+    _check(_lib.sparse_conv_get_launch(handle, N, H, W, stride, pad, arr), "sparse_conv_get_launch", handle)
+    names = ("V", "G", "B", "Cc", "WP", "WK", "KW", "lds_budget", "grid", "lds_bytes", "threads", "entries")
+    return dict(zip(names, list(arr)))
+
+
+def sparse_conv_destroy(handle: Optional[int]) -> None:
+    _lib.sparse_conv_destroy(handle)
+
+
+def raw_library():
+    """The loaded ctypes library (for tests of the raw ABI)."""
+    return _lib
+
+
+# ---------------------------------------------------------------- convenience wrapper
+
+class SparseConv:
+    """One pruned convolution layer on the GPU; owns a library handle."""
+
+    def __init__(self, dense_w: np.ndarray, mask: np.ndarray, dtype: str = "f32", unify: bool = False):
+        self.dtype = SC_F16 if dtype in ("f16", SC_F16) else SC_F32
+        self.K, self.C, self.R, self.S = dense_w.shape
+        self.handle = sparse_conv_create(dense_w, mask, self.dtype, SC_FLAG_UNIFY_NNZ if unify else 0)
+
+    def csr(self):
+        return sparse_conv_get_csr(self.handle, self.dtype)
+
+    def output_shape(self, H: int, W: int, stride: int = 1, pad: int = 0):
+        return sparse_conv_output_shape(self.handle, H, W, stride, pad)
+
+    def set_launch(self, params: Sequence[int]):
+        sparse_conv_set_launch(self.handle, params)
+
+    def get_launch(self, N, H, W, stride=1, pad=0):
+        return sparse_conv_get_launch(self.handle, N, H, W, stride, pad)
+
+    def forward(self, x, stride: int = 1, pad: int = 0, out=None):
+        """x: contiguous CUDA tensor [N][C][H][W] of the layer's dtype; returns [N][K][E][F]."""
+        import torch
+        want = torch.float16 if self.dtype == SC_F16 else torch.float32
+        if not x.is_cuda or x.dtype != want or not x.is_contiguous() or x.dim() != 4 or x.shape[1] != self.C:
+            raise ValueError("input must be a contiguous CUDA tensor [N][C][H][W] of the layer's dtype")
+        N, _, H, W = x.shape
+        E, F = self.output_shape(H, W, stride, pad)
+        if out is None:
+            out = torch.empty((N, self.K, E, F), dtype=want, device=x.device)
+        elif tuple(out.shape) != (N, self.K, E, F) or out.dtype != want or not out.is_contiguous():
+            raise ValueError("bad output tensor")
+        stream = torch.cuda.current_stream(x.device).cuda_stream
+        sparse_conv_forward(self.handle, x.data_ptr(), out.data_ptr(), N, H, W, stride, pad, stream)
+        return out
+
+    def close(self):
+        if getattr(self, "handle", None):
+            sparse_conv_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

@@ -1,0 +1,212 @@
+// C ABI of libsparseconv (declared in include/sparse_conv.h).
+#include <hip/hip_runtime_api.h>
+
+#include <cstring>
+#include <new>
+
+#include "../../include/sparse_conv.h"
+#include "internal.h"
+
+namespace sc {
+
+Plan::~Plan()
+{
+    if (d_entries) (void)hipFree(d_entries);
+    if (d_seg) (void)hipFree(d_seg);
+    if (d_krow) (void)hipFree(d_krow);
+}
+
+namespace {
+
+bool geometry_ok(const sparse_conv_s* h, int H, int W, int stride, int pad)
+{
+    if (H <= 0 || W <= 0 || stride < 1 || pad < 0) return false;
+    if (pad > (1 << 20) || H > (1 << 24) || W > (1 << 24)) return false;
+    return H + 2 * pad >= h->R && W + 2 * pad >= h->S;
+}
+
+int get_plan(sparse_conv_s* h, const Geometry& g, Plan** out)
+{
+    auto it = h->plans.find(g);
+    if (it == h->plans.end()) {
+        std::unique_ptr<Plan> p(new (std::nothrow) Plan());
+        if (!p) return SC_ENOMEM;
+        int rc = build_plan(h->csr, h->C, h->R, h->S, h->dtype == SC_F16 ? 2 : 4, g, h->over, *p);
+        if (rc != SC_OK) return rc;
+        it = h->plans.emplace(g, std::move(p)).first;
+    }
+    *out = it->second.get();
+    return SC_OK;
+}
+
+template <typename T>
+int upload(sparse_conv_s* h, const std::vector<T>& v, void** dst)
+{
+    const size_t bytes = std::max<size_t>(v.size(), 1) * sizeof(T);
+    hipError_t e = hipMalloc(dst, bytes);
+    if (e != hipSuccess) {
+        h->last_hip = (int)e;
+        *dst = nullptr;
+        return e == hipErrorOutOfMemory ? SC_ENOMEM : SC_EHIP;
+    }
+    if (!v.empty()) {
+        e = hipMemcpy(*dst, v.data(), v.size() * sizeof(T), hipMemcpyHostToDevice);
+        if (e != hipSuccess) {
+            h->last_hip = (int)e;
+            return SC_EHIP;
+        }
+    }
+    return SC_OK;
+}
+
+}  // namespace
+}  // namespace sc
+
+extern "C" {
+
+int sparse_conv_create(sparse_conv_t* out, const float* dense_w, const unsigned char* mask,
+                       int K, int C, int R, int S, int dtype, unsigned flags)
+{
+    if (!out || !dense_w || !mask) return SC_EINVAL;
+    if (K <= 0 || C <= 0 || R <= 0 || S <= 0) return SC_EINVAL;
+    if (dtype != SC_F32 && dtype != SC_F16) return SC_EINVAL;
+    if (flags & ~static_cast<unsigned>(SC_FLAG_UNIFY_NNZ)) return SC_EINVAL;
+    const long long L = (long long)C * R * S;
+    if (L >= (1ll << 31)) return SC_EINVAL;
+    try {
+        std::unique_ptr<sparse_conv_s> h(new sparse_conv_s());
+        h->K = K; h->C = C; h->R = R; h->S = S; h->L = (int)L;
+        h->dtype = dtype;
+        h->flags = flags;
+        if (!sc::encode_csr(dense_w, mask, K, (int)L, (flags & SC_FLAG_UNIFY_NNZ) != 0, dtype == SC_F16, h->csr))
+            return SC_EINVAL;
+        *out = h.release();
+        return SC_OK;
+    } catch (const std::bad_alloc&) {
+        return SC_ENOMEM;
+    } catch (...) {
+        return SC_ENOMEM;
+    }
+}
+
+int sparse_conv_output_shape(sparse_conv_t h, int H, int W, int stride, int pad, int* E, int* F)
+{
+    if (!h || !E || !F) return SC_EINVAL;
+    if (!sc::geometry_ok(h, H, W, stride, pad)) return SC_EINVAL;
+    *E = (H + 2 * pad - h->R) / stride + 1;
+    *F = (W + 2 * pad - h->S) / stride + 1;
+    return SC_OK;
+}
+
+int sparse_conv_get_csr(sparse_conv_t h, int* K, long long* nnz,
+                        const int** rowptr, const int** colidx, const void** values)
+{
+    if (!h) return SC_EINVAL;
+    if (K) *K = h->K;
+    if (nnz) *nnz = (long long)h->csr.colidx.size();
+    if (rowptr) *rowptr = h->csr.rowptr.data();
+    if (colidx) *colidx = h->csr.colidx.data();
+    if (values)
+        *values = h->dtype == SC_F16 ? static_cast<const void*>(h->csr.val16.data())
+                                     : static_cast<const void*>(h->csr.val32.data());
+    return SC_OK;
+}
+
+int sparse_conv_set_launch(sparse_conv_t h, const int* params, int nparams)
+{
+    if (!h || nparams < 0 || nparams > 8 || (nparams > 0 && !params)) return SC_EINVAL;
+    int v[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    for (int i = 0; i < nparams; ++i) {
+        if (params[i] < 0) return SC_EINVAL;
+        v[i] = params[i];
+    }
+    const int vmax = h->dtype == SC_F16 ? 8 : 4;
+    if (v[0] && (v[0] > vmax || (v[0] & (v[0] - 1)))) return SC_EINVAL;
+    if (v[6] && (v[6] > 16 || (v[6] & (v[6] - 1)))) return SC_EINVAL;
+    if (v[4] * (v[5] ? v[5] : 1) > 16 || v[5] > 16) return SC_EINVAL;
+    if (v[7] > 160 * 1024) return SC_EINVAL;
+    sc::Launch l;
+    l.V = v[0]; l.G = v[1]; l.B = v[2]; l.Cc = v[3]; l.WP = v[4]; l.WK = v[5]; l.KW = v[6]; l.lds_budget = v[7];
+    h->over = l;
+    h->plans.clear();
+    return SC_OK;
+}
+
+int sparse_conv_get_launch(sparse_conv_t h, int N, int H, int W, int stride, int pad, int* params)
+{
+    if (!h || !params || N < 0) return SC_EINVAL;
+    if (!sc::geometry_ok(h, H, W, stride, pad)) return SC_EINVAL;
+    try {
+        sc::Plan* p = nullptr;
+        int rc = sc::get_plan(h, sc::Geometry{N, H, W, stride, pad}, &p);
+        if (rc != SC_OK) return rc;
+        const int v[12] = {p->V, p->G, p->B, p->Cc, p->WP, p->WK, p->KW,
+                           h->over.lds_budget, p->grid, p->lds_bytes, p->threads, (int)p->entries.size()};
+        std::memcpy(params, v, sizeof(v));
+        return SC_OK;
+    } catch (...) {
+        return SC_ENOMEM;
+    }
+}
+
+int sparse_conv_forward(sparse_conv_t h, const void* input, void* output,
+                        int N, int H, int W, int stride, int pad, void* stream)
+{
+    if (!h || N < 0) return SC_EINVAL;
+    if (!sc::geometry_ok(h, H, W, stride, pad)) return SC_EINVAL;
+    if (N == 0) return SC_OK;
+    if (!input || !output || input == output) return SC_EINVAL;
+    if ((long long)N * h->K * (long long)H * W > (1ll << 40)) return SC_EINVAL;
+    try {
+        sc::Plan* p = nullptr;
+        int rc = sc::get_plan(h, sc::Geometry{N, H, W, stride, pad}, &p);
+        if (rc != SC_OK) return rc;
+        if (!p->uploaded) {
+            if ((rc = sc::upload(h, p->entries, &p->d_entries)) != SC_OK) return rc;
+            if ((rc = sc::upload(h, p->seg, &p->d_seg)) != SC_OK) return rc;
+            if ((rc = sc::upload(h, p->krow, &p->d_krow)) != SC_OK) return rc;
+            p->uploaded = true;
+        }
+        sc::KernelArgs a;
+        a.x = input;
+        a.y = output;
+        a.entries = static_cast<const sc::Entry*>(p->d_entries);
+        a.seg = static_cast<const int*>(p->d_seg);
+        a.krow = static_cast<const int*>(p->d_krow);
+        a.N = N; a.C = h->C; a.H = H; a.W = W; a.K = h->K; a.E = p->E; a.F = p->F;
+        a.stride = stride; a.pad = pad;
+        a.G = p->G; a.B = p->B; a.Cc = p->Cc; a.WP = p->WP; a.WK = p->WK;
+        a.Hb = p->Hb; a.Wp = p->Wp; a.PS = p->PS;
+        a.nchunks = p->nchunks; a.nbands = p->nbands; a.ngroups = p->ngroups;
+        a.ntiles = p->ntiles; a.kblocks = p->kblocks; a.slots = p->slots;
+        a.tile_elems = p->Cc * p->G * p->PS;
+        const int e = sc::launch_tile_kernel(h->dtype, p->V, p->KW, a, p->grid, p->threads, p->lds_bytes, stream);
+        if (e != 0) {
+            h->last_hip = e;
+            return SC_EHIP;
+        }
+        return SC_OK;
+    } catch (const std::bad_alloc&) {
+        return SC_ENOMEM;
+    } catch (...) {
+        return SC_EHIP;
+    }
+}
+
+int sparse_conv_last_hip_error(sparse_conv_t h) { return h ? h->last_hip : 0; }
+
+const char* sparse_conv_strerror(int code)
+{
+    switch (code) {
+        case SC_OK: return "ok";
+        case SC_EINVAL: return "invalid argument";
+        case SC_EUNSUPPORTED: return "configuration not supported by this build";
+        case SC_ENOMEM: return "out of memory";
+        case SC_EHIP: return "HIP runtime error";
+    }
+    return "unknown status";
+}
+
+void sparse_conv_destroy(sparse_conv_t h) { delete h; }
+
+}  // extern "C"

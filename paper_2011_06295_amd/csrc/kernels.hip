@@ -1,0 +1,218 @@
+// Direct sparse convolution tile kernel for gfx950 (CDNA4).
+//
+// What it computes (arXiv 2011.06295, section 3 eq. 1 restricted to the stored
+// weights of section 7; the kernel organisation replaces the one of section 8):
+//   Out[n][k][i][j] = sum over stored entries t of row k of
+//                     w[t] * Xpad[n][c_t][i*stride + r_t][j*stride + s_t]
+//
+// Organisation.  A workgroup owns one tile of the input: Cc channels of G image
+// groups (V images interleaved element-wise, so one LDS element is a V-vector
+// and is always naturally aligned whatever the tap shift), Hb rows with halo,
+// zero padding included.  The tile lives in LDS and is reused by every stored
+// weight of every output channel the workgroup handles.  A lane owns one
+// output position (group, row, column); a wavefront owns KW output channels
+// whose accumulators stay in registers across the channel chunks.  Stored
+// weights arrive as (weight, LDS offset) pairs, wave-uniform, fetched in
+// batches of kBatch through the scalar path; per pair a lane does one vector
+// LDS read and V fused multiply-adds in fp32.
+#include <hip/hip_runtime.h>
+
+#include "internal.h"
+
+namespace sc {
+
+template <typename T, int V>
+struct Vec {
+    typedef T type __attribute__((ext_vector_type(V)));
+    static __device__ __forceinline__ T get(const type& v, int i) { return v[i]; }
+    static __device__ __forceinline__ void set(type& v, int i, T x) { v[i] = x; }
+    static __device__ __forceinline__ type zero() { return type(T(0)); }
+};
+template <typename T>
+struct Vec<T, 1> {
+    typedef T type;
+    static __device__ __forceinline__ T get(const type& v, int) { return v; }
+    static __device__ __forceinline__ void set(type& v, int, T x) { v = x; }
+    static __device__ __forceinline__ type zero() { return T(0); }
+};
+
+template <typename T, int V, int KW>
+__global__ __launch_bounds__(1024) void tile_kernel(const KernelArgs a)
+{
+    using VT = Vec<T, V>;
+    using vec = typename VT::type;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    vec* tile = reinterpret_cast<vec*>(smem);
+
+    const int tid = threadIdx.x;
+    const int nthreads = blockDim.x;
+
+    // Workgroup -> (tile, channel block).  Consecutive workgroup ids go round
+    // the 8 XCDs; all channel blocks of one tile are kept on one XCD so the
+    // tile's input is fetched into a single L2.
+    const int bid = blockIdx.x;
+    const int xcd = bid & 7;
+    const int q = bid >> 3;
+    const int kb = q % a.kblocks;
+    const int tile_id = (q / a.kblocks) * 8 + xcd;
+    if (tile_id >= a.ntiles) return;
+    const int tg = tile_id / a.nbands;
+    const int band = tile_id - tg * a.nbands;
+    const int g0 = tg * a.G;            // first image group of the tile
+    const int i0 = band * a.B;          // first output row of the tile
+    const int y0 = i0 * a.stride - a.pad;  // input row held by tile row 0 (may be negative)
+
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int lane = tid & 63;
+    const int wp = wave % a.WP;
+    const int wk = wave / a.WP;
+
+    // lane -> output position
+    const int slot = wp * 64 + lane;
+    const int bf = a.B * a.F;
+    const int g = slot / bf;
+    const int rem = slot - g * bf;
+    const int i = rem / a.F;
+    const int j = rem - i * a.F;
+    const bool valid = slot < a.slots && (i0 + i) < a.E && (g0 + g) < a.ngroups;
+    const int base = valid ? g * a.PS + (i * a.stride) * a.Wp + j * a.stride : 0;
+
+    float acc[KW][V];
+#pragma unroll
+    for (int kk = 0; kk < KW; ++kk)
+#pragma unroll
+        for (int v = 0; v < V; ++v) acc[kk][v] = 0.f;
+
+    // halo, padding and absent images stay zero for the whole kernel
+    for (int u = tid; u < a.tile_elems; u += nthreads) tile[u] = VT::zero();
+
+    const int ya = y0 > 0 ? y0 : 0;
+    const int yb = (y0 + a.Hb) < a.H ? (y0 + a.Hb) : a.H;
+    const int rows = yb - ya;
+    const T* __restrict__ x = static_cast<const T*>(a.x);
+    const size_t img_stride = (size_t)a.C * a.H * a.W;
+
+    for (int ch = 0; ch < a.nchunks; ++ch) {
+        __syncthreads();  // zero fill done / previous chunk fully consumed
+        // ---- stage the chunk: interior elements only, V images per element
+        const int c0 = ch * a.Cc;
+        const int cn = (a.C - c0) < a.Cc ? (a.C - c0) : a.Cc;
+        if (rows > 0) {
+            const int per_c = rows * a.W;
+            const int per_g = cn * per_c;
+            const int total = a.G * per_g;
+            for (int u = tid; u < total; u += nthreads) {
+                const int gg = u / per_g;
+                const int r1 = u - gg * per_g;
+                const int c = r1 / per_c;
+                const int r2 = r1 - c * per_c;
+                const int yy = r2 / a.W;
+                const int xx = r2 - yy * a.W;
+                const int grp = g0 + gg;
+                if (grp >= a.ngroups) continue;
+                const size_t src = ((size_t)(c0 + c) * a.H + (ya + yy)) * a.W + xx;
+                vec val;
+#pragma unroll
+                for (int v = 0; v < V; ++v) {
+                    const int n = grp * V + v;
+                    VT::set(val, v, n < a.N ? x[(size_t)n * img_stride + src] : T(0));
+                }
+                tile[(c * a.G + gg) * a.PS + (ya - y0 + yy) * a.Wp + a.pad + xx] = val;
+            }
+        }
+        __syncthreads();
+
+        // ---- gather-FMA over this wavefront's KW rows
+        const int* __restrict__ sg = a.seg + (((size_t)kb * a.nchunks + ch) * a.WK + wk) * (KW * 2);
+#pragma unroll
+        for (int kk = 0; kk < KW; ++kk) {
+            const int start = sg[2 * kk];
+            const int nb = sg[2 * kk + 1];
+            const Entry* __restrict__ e = a.entries + start;
+            for (int b = 0; b < nb; ++b, e += kBatch) {
+                Entry ev[kBatch];
+#pragma unroll
+                for (int u = 0; u < kBatch; ++u) ev[u] = e[u];
+#pragma unroll
+                for (int u = 0; u < kBatch; ++u) {
+                    const vec xv = tile[base + ev[u].off];
+                    const float w = __uint_as_float(ev[u].wbits);
+#pragma unroll
+                    for (int v = 0; v < V; ++v)
+                        acc[kk][v] = __builtin_fmaf(w, (float)VT::get(xv, v), acc[kk][v]);
+                }
+            }
+        }
+    }
+
+    // ---- store: one writer per output element
+    if (valid) {
+        T* __restrict__ y = static_cast<T*>(a.y);
+        const int* __restrict__ kr = a.krow + ((size_t)kb * a.WK + wk) * KW;
+        const size_t plane = (size_t)a.E * a.F;
+        const size_t pix = (size_t)(i0 + i) * a.F + j;
+#pragma unroll
+        for (int kk = 0; kk < KW; ++kk) {
+            const int k = kr[kk];
+            if (k < 0) continue;
+#pragma unroll
+            for (int v = 0; v < V; ++v) {
+                const int n = (g0 + g) * V + v;
+                if (n < a.N) y[((size_t)n * a.K + k) * plane + pix] = (T)acc[kk][v];
+            }
+        }
+    }
+}
+
+namespace {
+
+template <typename T, int V, int KW>
+int launch_one(const KernelArgs& a, int grid, int threads, int lds_bytes, hipStream_t s)
+{
+    auto fn = tile_kernel<T, V, KW>;
+    if (lds_bytes > 64 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(fn),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+        if (e != hipSuccess) return (int)e;
+    }
+    hipLaunchKernelGGL(fn, dim3(grid), dim3(threads), lds_bytes, s, a);
+    return (int)hipGetLastError();
+}
+
+template <typename T, int V>
+int launch_kw(int KW, const KernelArgs& a, int grid, int threads, int lds, hipStream_t s)
+{
+    switch (KW) {
+        case 1: return launch_one<T, V, 1>(a, grid, threads, lds, s);
+        case 2: return launch_one<T, V, 2>(a, grid, threads, lds, s);
+        case 4: return launch_one<T, V, 4>(a, grid, threads, lds, s);
+        case 8: return launch_one<T, V, 8>(a, grid, threads, lds, s);
+        case 16: return launch_one<T, V, 16>(a, grid, threads, lds, s);
+    }
+    return (int)hipErrorInvalidValue;
+}
+
+}  // namespace
+
+int launch_tile_kernel(int dtype, int V, int KW, const KernelArgs& a, int grid, int threads,
+                       int lds_bytes, void* stream)
+{
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (dtype == 0) {
+        switch (V) {
+            case 1: return launch_kw<float, 1>(KW, a, grid, threads, lds_bytes, s);
+            case 2: return launch_kw<float, 2>(KW, a, grid, threads, lds_bytes, s);
+            case 4: return launch_kw<float, 4>(KW, a, grid, threads, lds_bytes, s);
+        }
+    } else {
+        switch (V) {
+            case 1: return launch_kw<_Float16, 1>(KW, a, grid, threads, lds_bytes, s);
+            case 2: return launch_kw<_Float16, 2>(KW, a, grid, threads, lds_bytes, s);
+            case 4: return launch_kw<_Float16, 4>(KW, a, grid, threads, lds_bytes, s);
+            case 8: return launch_kw<_Float16, 8>(KW, a, grid, threads, lds_bytes, s);
+        }
+    }
+    return (int)hipErrorInvalidValue;
+}
+
+}  // namespace sc

@@ -1,0 +1,111 @@
+"""CPU-side tests of libsparseconv: the library loads, exports what the header
+declares, encodes the CSR of section 7 bit-exactly like the oracle, validates
+its arguments and plans launches without a GPU.  No kernel is launched here."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2011_06295_amd import binding as B
+from helpers import rand_layer
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "sparse_conv.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = set(re.findall(r"\b(sparse_conv_[a-z_0-9]+)\s*\(", hdr))
+    assert declared == set(B.EXPORTS)
+    lib = C.CDLL(B.LIB_PATH)
+    for name in declared:
+        assert getattr(lib, name) is not None
+
+
+@pytest.mark.parametrize("seed", range(6))
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+@pytest.mark.parametrize("unify", [False, True])
+def test_csr_is_bit_exact_against_the_oracle(seed, dtype, unify):
+    rng = np.random.default_rng(300 + seed)
+    K, Cc, R, S = int(rng.integers(1, 20)), int(rng.integers(1, 12)), int(rng.integers(1, 4)), int(rng.integers(1, 4))
+    w, m, _ = rand_layer(rng, 1, Cc, K, R, S, 4, 4, density=float(rng.random()))
+    if seed == 0:
+        m[0] = 0
+    if seed == 1:
+        w *= 1e-6   # binary16 subnormals
+    if seed == 2:
+        w.reshape(-1)[:3] = [0.0, -0.0, 70000.0]
+        m.reshape(-1)[:3] = 1
+    layer = B.SparseConv(w, m, dtype=dtype, unify=unify)
+    rowptr, colidx, values = layer.csr()
+    om = oracle.unify_mask(m)[0] if unify else m
+    orow, ocol, oval = oracle.csr_encode(w, om)
+    assert rowptr.tobytes() == orow.tobytes()
+    assert colidx.tobytes() == ocol.tobytes()
+    if dtype == "f16":
+        assert values.dtype == np.uint16 and values.tobytes() == oracle.f32_to_f16_bits(oval).tobytes()
+    else:
+        assert values.dtype == np.float32 and values.tobytes() == oval.tobytes()
+    layer.close()
+
+
+def test_config_layers_encode_like_the_oracle():
+    from paper_2011_06295_amd import workloads as wl
+    for cfg, layer_id, spec in [(1, 1, wl.config1().layers[0]), (2, 2, wl.lenet5().layers[1]), (3, 5, wl.vgg16().layers[4])]:
+        w, m = wl.make_weights(cfg, layer_id, spec), wl.make_mask(cfg, layer_id, spec)
+        for dtype in ("f32", "f16"):
+            layer = B.SparseConv(w, m, dtype=dtype)
+            rowptr, colidx, values = layer.csr()
+            orow, ocol, oval = oracle.csr_encode(w, m)
+            assert rowptr.tobytes() == orow.tobytes() and colidx.tobytes() == ocol.tobytes()
+            want = oracle.f32_to_f16_bits(oval) if dtype == "f16" else oval
+            assert values.tobytes() == want.tobytes()
+            layer.close()
+
+
+def test_argument_validation_returns_status_codes():
+    lib = B.raw_library()
+    w = np.ones((2, 3, 3, 3), dtype=np.float32)
+    m = np.ones((2, 3, 3, 3), dtype=np.uint8)
+    h = C.c_void_p()
+    assert lib.sparse_conv_create(None, w.ctypes.data, m.ctypes.data, 2, 3, 3, 3, 0, 0) == B.SC_EINVAL
+    assert lib.sparse_conv_create(C.byref(h), None, m.ctypes.data, 2, 3, 3, 3, 0, 0) == B.SC_EINVAL
+    assert lib.sparse_conv_create(C.byref(h), w.ctypes.data, m.ctypes.data, 0, 3, 3, 3, 0, 0) == B.SC_EINVAL
+    assert lib.sparse_conv_create(C.byref(h), w.ctypes.data, m.ctypes.data, 2, 3, 3, 3, 7, 0) == B.SC_EINVAL
+    assert lib.sparse_conv_create(C.byref(h), w.ctypes.data, m.ctypes.data, 2, 3, 3, 3, 0, 8) == B.SC_EINVAL
+    assert h.value is None
+    assert lib.sparse_conv_create(C.byref(h), w.ctypes.data, m.ctypes.data, 2, 3, 3, 3, 0, 0) == B.SC_OK
+    e, f = C.c_int(-7), C.c_int(-7)
+    assert lib.sparse_conv_output_shape(h, 2, 2, 1, 0, C.byref(e), C.byref(f)) == B.SC_EINVAL   # filter larger than input
+    assert (e.value, f.value) == (-7, -7)
+    assert lib.sparse_conv_output_shape(h, 5, 5, 0, 0, C.byref(e), C.byref(f)) == B.SC_EINVAL   # stride < 1
+    assert lib.sparse_conv_output_shape(h, 5, 5, 1, -1, C.byref(e), C.byref(f)) == B.SC_EINVAL  # pad < 0
+    assert lib.sparse_conv_output_shape(h, 8, 7, 2, 1, C.byref(e), C.byref(f)) == B.SC_OK
+    assert (e.value, f.value) == (oracle.output_dim(8, 1, 3, 2), oracle.output_dim(7, 1, 3, 2)) == (4, 4)
+    # forward: bad geometry / null buffers are rejected before anything touches a GPU
+    assert lib.sparse_conv_forward(h, None, None, 1, 2, 2, 1, 0, None) == B.SC_EINVAL
+    assert lib.sparse_conv_forward(h, None, None, 1, 8, 8, 1, 1, None) == B.SC_EINVAL
+    assert lib.sparse_conv_forward(h, None, None, -1, 8, 8, 1, 1, None) == B.SC_EINVAL
+    assert lib.sparse_conv_forward(None, None, None, 1, 8, 8, 1, 1, None) == B.SC_EINVAL
+    assert lib.sparse_conv_forward(h, None, None, 0, 8, 8, 1, 1, None) == B.SC_OK               # empty batch: no-op
+    bad = (C.c_int * 8)(3, 0, 0, 0, 0, 0, 0, 0)
+    assert lib.sparse_conv_set_launch(h, bad, 8) == B.SC_EINVAL                                  # V must be a power of two
+    assert lib.sparse_conv_strerror(B.SC_EINVAL) == b"invalid argument"
+    lib.sparse_conv_destroy(h)
+    lib.sparse_conv_destroy(None)
+
+
+def test_launch_plans_fit_the_hardware():
+    from paper_2011_06295_amd import workloads as wl
+    for work, n in [(wl.vgg16(), 128), (wl.vgg16(dtype="f16"), 256), (wl.lenet5(), 64), (wl.sweep_layer(9000, False), 256)]:
+        for li, spec in enumerate(work.layers, 1):
+            w, m = wl.make_weights(work.config, li, spec), wl.make_mask(work.config, li, spec)
+            layer = B.SparseConv(w, m, dtype=work.dtype)
+            p = layer.get_launch(n, spec.H, spec.W, spec.stride, spec.pad)
+            assert 64 <= p["threads"] <= 1024 and p["threads"] % 64 == 0
+            assert 0 < p["lds_bytes"] <= 160 * 1024
+            assert p["grid"] >= 1
+            layer.close()

@@ -1,0 +1,136 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle,
+element by element, on seeded inputs.  fp32 tolerance 1e-5, fp16 2e-3
+(|got-ref| <= tol*|ref| + tol*max|ref|)."""
+import numpy as np
+import pytest
+
+import oracle
+from helpers import TOL, assert_close, rand_layer
+
+pytestmark = pytest.mark.gpu
+
+
+def _torch():
+    import torch
+    return torch
+
+
+def run_gpu(layer, x, stride, pad, dtype):
+    torch = _torch()
+    xt = torch.from_numpy(x).cuda()
+    if dtype == "f16":
+        xt = xt.half()
+    y = layer.forward(xt.contiguous(), stride, pad)
+    torch.cuda.synchronize()
+    return y.float().cpu().numpy()
+
+
+def oracle_ref(w, m, x, stride, pad, dtype, unify=False):
+    K, _, R, S = w.shape
+    mm = oracle.unify_mask(m)[0] if unify else m
+    rowptr, colidx, values = oracle.csr_encode(w, mm)
+    if dtype == "f16":   # same binary16-rounded operands, wide accumulation
+        values = oracle.round_through_f16(values)
+        x = oracle.round_through_f16(x)
+    return oracle.sparse_conv((rowptr, colidx, values), x, K, R, S, stride, pad)
+
+
+def check(w, m, x, stride, pad, dtype, unify=False, launch=None, what=""):
+    from paper_2011_06295_amd import binding as B
+    layer = B.SparseConv(w, m, dtype=dtype, unify=unify)
+    if launch is not None:
+        layer.set_launch(launch)
+    N, _, H, W = x.shape
+    print(what, "launch", layer.get_launch(N, H, W, stride, pad), flush=True)
+    got = run_gpu(layer, x, stride, pad, dtype)
+    ref = oracle_ref(w, m, x, stride, pad, dtype, unify)
+    assert_close(got, ref, TOL[dtype], what)
+    layer.close()
+    return got
+
+
+def _shapes():
+    rng = np.random.default_rng(77)
+    out = []
+    for t in range(24):
+        R, S = int(rng.choice([1, 2, 3, 5])), int(rng.choice([1, 2, 3, 5]))
+        st, p = int(rng.integers(1, 4)), int(rng.integers(0, 3))
+        H, W = int(rng.integers(1, 20)), int(rng.integers(1, 20))
+        if H + 2 * p < R or W + 2 * p < S:
+            H, W = H + R, W + S
+        out.append((int(rng.integers(1, 12)), int(rng.integers(1, 24)), int(rng.integers(1, 40)), R, S, H, W, st, p))
+    return out
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+@pytest.mark.parametrize("shape", _shapes())
+def test_random_small_layers(shape, dtype):
+    N, C, K, R, S, H, W, st, p = shape
+    rng = np.random.default_rng(abs(hash(shape)) % (2 ** 32))
+    w, m, x = rand_layer(rng, N, C, K, R, S, H, W, density=float(rng.choice([0.05, 0.3, 1.0])))
+    check(w, m, x, st, p, dtype, what=f"shape{shape}-{dtype}")
+
+
+LAUNCHES = [
+    # V, G, B, Cc, WP, WK, KW, lds
+    [1, 1, 0, 0, 0, 1, 1, 0],
+    [1, 2, 3, 2, 0, 2, 2, 0],
+    [2, 3, 2, 5, 0, 4, 4, 0],
+    [4, 2, 0, 3, 0, 2, 16, 0],
+    [4, 1, 5, 16, 0, 1, 8, 0],
+    [2, 4, 4, 1, 0, 3, 2, 0],
+]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+@pytest.mark.parametrize("launch", LAUNCHES, ids=lambda l: "-".join(map(str, l)))
+def test_launch_overrides_do_not_change_the_result(launch, dtype):
+    """Several tiles, several channel chunks, ragged tails in every dimension."""
+    rng = np.random.default_rng(5150)
+    N, C, K, R, S, H, W = 11, 13, 37, 3, 3, 13, 11
+    w, m, x = rand_layer(rng, N, C, K, R, S, H, W, density=0.25)
+    m[3] = 0     # an output channel without stored weights must still be written (as zeros)
+    m[7] = 1     # a full row
+    got = check(w, m, x, 1, 1, dtype, launch=launch, what=f"launch{launch}-{dtype}")
+    assert not got[:, 3].any()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+def test_degenerate_cases(dtype):
+    rng = np.random.default_rng(99)
+    # all-zero mask: output exactly zero
+    w, m, x = rand_layer(rng, 3, 4, 5, 3, 3, 6, 6)
+    got = check(w, m * 0, x, 1, 1, dtype, what="zero-mask")
+    assert not got.any()
+    # dense mask (0 % sparsity) equals dense convolution
+    check(w, np.ones_like(m), x, 1, 1, dtype, what="dense-mask")
+    # unify flag: same numbers
+    check(w, m, x, 1, 1, dtype, unify=True, what="unify")
+    # single pixel output, filter as large as the padded input
+    w2, m2, x2 = rand_layer(rng, 2, 3, 4, 5, 5, 3, 3, density=0.5)
+    check(w2, m2, x2, 1, 1, dtype, what="filter==padded-input")
+    # 1x1 filter, K = C = 1
+    w3, m3, x3 = rand_layer(rng, 5, 1, 1, 1, 1, 7, 9, density=1.0)
+    check(w3, m3, x3, 2, 0, dtype, what="1x1")
+
+
+def test_hand_examples_on_gpu():
+    import json
+    import os
+    g = json.load(open(os.path.join(os.path.dirname(__file__), "golden", "hand_3x3.json")))
+    x = np.array(g["x"], dtype=np.float32).reshape(1, 1, 3, 3)
+    for case in g["cases"]:
+        w = np.array(case["w"], dtype=np.float32).reshape(1, 1, 3, 3)
+        m = np.array(case["mask"], dtype=np.uint8).reshape(1, 1, 3, 3)
+        for dtype in ("f32", "f16"):
+            got = check(w, m, x, case["stride"], case["pad"], dtype, what=case["name"])
+            assert got[0, 0].tolist() == [[float(v) for v in row] for row in case["out"]]
+
+
+def test_config1_single_layer():
+    from paper_2011_06295_amd import workloads as wl
+    work = wl.config1()
+    spec = work.layers[0]
+    w, m = wl.make_weights(1, 1, spec), wl.make_mask(1, 1, spec)
+    x = wl.make_input(work)
+    check(w, m, x, spec.stride, spec.pad, "f32", what="config1")
