@@ -1,0 +1,191 @@
+#!/usr/bin/env python3
+"""Benchmark of direct sparse convolution on one MI355X.
+
+A step is one pass of the hot path over one batch: the sparse convolution of
+every layer of the workload on its resident (already in HBM) input.  Prints one
+JSON line: effective GFLOP/s = 2 * stored weights * E * F * N / time, the
+roofline position of the tile kernel, per-layer figures and the CPU oracle
+timed on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+# MI355X published peaks used for the roofline
+HBM_PEAK = 8.0e12                      # B/s
+LDS_PEAK = 256 * 256 * 2.4e9           # 256 CUs x 256 B/clk (wide LDS reads) x 2.4 GHz = 157.3 TB/s
+VALU_PEAK_FMA = 256 * 128 * 2.4e9      # fp32 vector: 157.3 TFLOP/s = 78.6e12 FMA/s
+
+
+def make_workload(name: str):
+    from paper_2011_06295_amd import workloads as wl
+    if name == "vgg16_f32":
+        return wl.vgg16(128, "f32"), None
+    if name == "vgg16_f16":
+        return wl.vgg16(256, "f16"), None
+    if name == "lenet5":
+        return wl.lenet5(64), None
+    if name == "config1":
+        return wl.config1(), None
+    if name.startswith("sweep"):      # sweep90, sweep95r (r = ragged rows)
+        ragged = name.endswith("r")
+        s = int(name[5:].rstrip("r")) * 100
+        return wl.sweep_layer(s, ragged), [wl.sweep_layer_index(s, ragged)]
+    raise SystemExit(f"unknown workload {name}")
+
+
+def layer_roofs(run, N, b):
+    s = run.spec
+    macs = run.macs(N)
+    hbm_bytes = N * s.C * s.H * s.W * b + N * s.K * s.E * s.F * b + run.nnz * (b + 4) + (s.K + 1) * 4
+    return {
+        "macs": macs,
+        "hbm_bytes": hbm_bytes,
+        "lds_bytes": macs * b,
+        "t_hbm": hbm_bytes / HBM_PEAK,
+        "t_lds": macs * b / LDS_PEAK,
+        "t_valu": macs / VALU_PEAK_FMA,
+    }
+
+
+def cpu_baseline(net, work, budget_s=12.0):
+    """The oracle (float accumulation, one thread) on the first n images of every layer."""
+    import oracle
+    # operands exactly as the GPU saw them
+    ins = [r.x.float().cpu().numpy() for r in net.runs]
+
+    def run_sample(n):
+        t0 = time.perf_counter()
+        macs = 0
+        for r, (w, m), x in zip(net.runs, net.host_weights, ins):
+            csr = oracle.csr_encode(w, m)
+            oracle.sparse_conv(csr, x[:n], r.spec.K, r.spec.R, r.spec.S, r.spec.stride, r.spec.pad, acc="f32")
+            macs += r.macs(n)
+        return time.perf_counter() - t0, macs
+
+    t1, m1 = run_sample(1)
+    n = int(max(1, min(work.N, budget_s / max(t1, 1e-6))))
+    if n > 1:
+        t, macs = run_sample(n)
+    else:
+        t, macs = t1, m1
+    return {
+        "value": 2.0 * macs / t / 1e9, "unit": "GFLOP/s", "cores": 1, "kind": "oracle",
+        "sample": f"first {n} of {work.N} images through all {len(net.runs)} layers "
+                  f"({macs:.3g} MACs in {t:.1f} s, float accumulation, single thread)",
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="vgg16_f32")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--launch", default="", help="comma separated launch override applied to every layer")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        raise SystemExit("bench.py: this build runs on one GPU only (the path shards by batch with no exchange "
+                         "step; no multi-GPU figure is produced). Use --gpus 1.")
+
+    import torch
+    if not torch.cuda.is_available():
+        raise SystemExit("bench.py needs a GPU (there is no CPU fallback of the product path)")
+    from paper_2011_06295_amd import harness, workloads as wl
+
+    work, layer_ids = make_workload(args.workload)
+    net = harness.Network(work, layer_ids=layer_ids)
+    if args.launch:
+        for r in net.runs:
+            r.layer.set_launch([int(v) for v in args.launch.split(",")])
+    net.run_chain(wl.make_input(work))
+    N = work.N
+    b = 2 if work.dtype == "f16" else 4
+
+    for _ in range(args.warmup):
+        net.step()
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record()
+    for _ in range(args.steps):
+        net.step()
+    ev1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    gpu_ms = ev0.elapsed_time(ev1)
+    ms_per_step = wall * 1e3 / args.steps
+
+    # per-layer durations: events around each launch on the launch stream
+    reps = max(10, min(args.steps, 50))
+    layers = []
+    for r in net.runs:
+        for _ in range(3):
+            r.layer.forward(r.x, r.spec.stride, r.spec.pad, out=r.y)
+        a, z = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(reps):
+            r.layer.forward(r.x, r.spec.stride, r.spec.pad, out=r.y)
+        z.record()
+        torch.cuda.synchronize()
+        t = a.elapsed_time(z) * 1e-3 / reps
+        roofs = layer_roofs(r, N, b)
+        bound = max(("hbm", roofs["t_hbm"]), ("lds", roofs["t_lds"]), ("alu", roofs["t_valu"]), key=lambda kv: kv[1])
+        layers.append({
+            "name": r.spec.name, "shape": f"{r.spec.C}x{r.spec.H}x{r.spec.W}->{r.spec.K}",
+            "nnz": r.nnz, "us": round(t * 1e6, 2), "gflops": round(2 * roofs["macs"] / t / 1e9, 1),
+            "bound": bound[0], "roof_frac": round(bound[1] / t, 4),
+            "hbm_GBs": round(roofs["hbm_bytes"] / t / 1e9, 1), "lds_GBs": round(roofs["lds_bytes"] / t / 1e9, 1),
+            "launch": {k: v for k, v in r.layer.get_launch(N, r.spec.H, r.spec.W, r.spec.stride, r.spec.pad).items()
+                       if k in ("V", "G", "B", "Cc", "WP", "WK", "KW", "grid", "lds_bytes")},
+        })
+
+    total_macs = net.total_macs()
+    roofs = [layer_roofs(r, N, b) for r in net.runs]
+    nl = len(net.runs)
+    avg_launch_s = gpu_ms * 1e-3 / (args.steps * nl)
+    sums = {k: sum(rf[k] for rf in roofs) for k in ("t_hbm", "t_lds", "t_valu", "lds_bytes", "hbm_bytes")}
+    if sums["t_lds"] >= sums["t_hbm"]:
+        roofline = {"bound": "lds", "achieved": sums["lds_bytes"] / nl / avg_launch_s / 1e9, "peak": LDS_PEAK / 1e9,
+                    "unit": "GB/s"}
+    else:
+        roofline = {"bound": "hbm", "achieved": sums["hbm_bytes"] / nl / avg_launch_s / 1e9, "peak": HBM_PEAK / 1e9,
+                    "unit": "GB/s"}
+    roofline["frac"] = roofline["achieved"] / roofline["peak"]
+    roofline["traffic"] = None
+    roofline["kernel"] = "sc::tile_kernel"
+    roofline["avg_launch_us"] = avg_launch_s * 1e6
+    roofline["launches_per_step"] = nl
+    roofline["hbm_frac"] = sums["hbm_bytes"] / nl / avg_launch_s / HBM_PEAK
+    roofline["alu_frac"] = total_macs / nl / avg_launch_s / VALU_PEAK_FMA
+
+    out = {
+        "metric": "effective GFLOP/s (2*nnz*E*F*N over the sparse conv layers of the workload)",
+        "value": 2.0 * total_macs / (ms_per_step * 1e-3) / 1e9,
+        "unit": "GFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "gpu_ms_per_step": gpu_ms / args.steps,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": work.dtype, "data": "synthetic",
+        "config": {"workload": f"{work.name}, batch {N}, {nl} sparse conv layer(s), conv only, inputs resident in HBM",
+                   "layers": nl, "batch": N, "total_macs": total_macs},
+        "roofline": roofline,
+        "layers": layers,
+    }
+    if not args.no_cpu:
+        out["cpu_baseline"] = cpu_baseline(net, work)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

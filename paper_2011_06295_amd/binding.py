@@ -39,6 +39,10 @@ def _load():
         raise ImportError(
             f"{LIB_PATH} is missing: build it with `python -m paper_2011_06295_amd.build` "
             "(there is no CPU fallback)")
+    # PyTorch bundles its own HIP runtime (same SONAME as the system one).  It has
+    # to be in the process before this library is loaded, so that both resolve to
+    # one runtime and device pointers and streams can be shared.
+    import torch  # noqa: F401
     lib = C.CDLL(LIB_PATH)
     vp, ip = C.c_void_p, C.POINTER(C.c_int)
     lib.sparse_conv_create.argtypes = [C.POINTER(vp), vp, vp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_uint]

@@ -1,0 +1,80 @@
+"""Runs a synthetic workload (a stack of pruned conv layers) through the library.
+
+Only the convolutions are the library's; ReLU and 2x2 max-pool between layers
+(section 3 of the paper: bias/activation follow the convolution and are not
+part of the sparse kernel of section 8) are plain torch ops on the same stream.
+"""
+from __future__ import annotations
+
+from typing import List, Optional
+
+import numpy as np
+
+from . import binding as B
+from . import workloads as wl
+
+
+class LayerRun:
+    def __init__(self, spec: wl.LayerSpec, layer: B.SparseConv, nnz: int):
+        self.spec = spec
+        self.layer = layer
+        self.nnz = nnz
+        self.x = None   # resident device input  [N][C][H][W]
+        self.y = None   # resident device output [N][K][E][F]
+
+    def macs(self, N: int) -> int:
+        return self.nnz * self.spec.E * self.spec.F * N
+
+
+class Network:
+    """Handles of all layers of a workload plus their resident activations."""
+
+    def __init__(self, work: wl.Workload, unify: bool = False, layer_ids: Optional[List[int]] = None):
+        self.work = work
+        self.runs: List[LayerRun] = []
+        self.host_weights = []
+        for li, spec in enumerate(work.layers, 1):
+            lid = layer_ids[li - 1] if layer_ids else li
+            w = wl.make_weights(work.config, lid, spec)
+            m = wl.make_mask(work.config, lid, spec)
+            layer = B.SparseConv(w, m, dtype=work.dtype, unify=unify)
+            rowptr = layer.csr()[0]
+            self.runs.append(LayerRun(spec, layer, int(rowptr[-1])))
+            self.host_weights.append((w, m))
+
+    def torch_dtype(self):
+        import torch
+        return torch.float16 if self.work.dtype == "f16" else torch.float32
+
+    def glue(self, spec: wl.LayerSpec, y):
+        import torch.nn.functional as F
+        if spec.pool_after and spec.pool_before_relu:
+            y = F.max_pool2d(y, 2)
+        if spec.relu_after:
+            y = F.relu(y)
+        if spec.pool_after and not spec.pool_before_relu:
+            y = F.max_pool2d(y, 2)
+        return y.contiguous()
+
+    def run_chain(self, x0: np.ndarray):
+        """Pushes x0 through every layer once, keeping each layer's input and output on the device."""
+        import torch
+        x = torch.from_numpy(x0).cuda().to(self.torch_dtype()).contiguous()
+        for run in self.runs:
+            run.x = x
+            run.y = run.layer.forward(x, run.spec.stride, run.spec.pad)
+            x = self.glue(run.spec, run.y)
+        torch.cuda.synchronize()
+        return x
+
+    def step(self):
+        """One pass of the hot path: every layer's convolution on its resident input."""
+        for run in self.runs:
+            run.layer.forward(run.x, run.spec.stride, run.spec.pad, out=run.y)
+
+    def total_macs(self) -> int:
+        return sum(r.macs(self.work.N) for r in self.runs)
+
+    def close(self):
+        for r in self.runs:
+            r.layer.close()
