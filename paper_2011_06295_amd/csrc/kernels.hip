@@ -21,6 +21,19 @@
 
 namespace sc {
 
+// Read-only plan tables are addressed through the constant address space: a
+// wave-uniform load from it is always issued on the scalar path (s_load), which
+// an ordinary global pointer loses once a barrier sits between store and load.
+#define SC_CONSTANT __attribute__((address_space(4)))
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Wold-style-cast"
+template <typename T>
+__device__ __forceinline__ const SC_CONSTANT T* as_constant(const T* p)
+{
+    return (const SC_CONSTANT T*)(p);
+}
+#pragma clang diagnostic pop
+
 template <typename T, int V>
 struct Vec {
     typedef T type __attribute__((ext_vector_type(V)));
@@ -123,24 +136,39 @@ __global__ __launch_bounds__(1024) void tile_kernel(const KernelArgs a)
         __syncthreads();
 
         // ---- gather-FMA over this wavefront's KW rows
-        const int* __restrict__ sg = a.seg + (((size_t)kb * a.nchunks + ch) * a.WK + wk) * (KW * 2);
+        const SC_CONSTANT int* sg = as_constant(a.seg) + (((size_t)kb * a.nchunks + ch) * a.WK + wk) * (KW * 2);
 #pragma unroll
         for (int kk = 0; kk < KW; ++kk) {
             const int start = sg[2 * kk];
             const int nb = sg[2 * kk + 1];
-            const Entry* __restrict__ e = a.entries + start;
-            for (int b = 0; b < nb; ++b, e += kBatch) {
-                Entry ev[kBatch];
+            const SC_CONSTANT Entry* e = as_constant(a.entries) + start;
+            Entry cur[kBatch];
 #pragma unroll
-                for (int u = 0; u < kBatch; ++u) ev[u] = e[u];
+            for (int u = 0; u < kBatch; ++u) {  // the table ends in kBatch slack entries
+                cur[u].wbits = e[u].wbits;
+                cur[u].off = e[u].off;
+            }
+            for (int b = 0; b < nb; ++b) {
+                vec xv[kBatch];
+#pragma unroll
+                for (int u = 0; u < kBatch; ++u) xv[u] = tile[base + cur[u].off];
+                e += kBatch;
+                Entry nxt[kBatch];  // look-ahead fetch of the next batch
 #pragma unroll
                 for (int u = 0; u < kBatch; ++u) {
-                    const vec xv = tile[base + ev[u].off];
-                    const float w = __uint_as_float(ev[u].wbits);
+                    nxt[u].wbits = e[u].wbits;
+                    nxt[u].off = e[u].off;
+                }
+                __builtin_amdgcn_sched_barrier(0);  // keep the LDS reads ahead of the arithmetic
+#pragma unroll
+                for (int u = 0; u < kBatch; ++u) {
+                    const float w = __uint_as_float(cur[u].wbits);
 #pragma unroll
                     for (int v = 0; v < V; ++v)
-                        acc[kk][v] = __builtin_fmaf(w, (float)VT::get(xv, v), acc[kk][v]);
+                        acc[kk][v] = __builtin_fmaf(w, (float)VT::get(xv[u], v), acc[kk][v]);
                 }
+#pragma unroll
+                for (int u = 0; u < kBatch; ++u) cur[u] = nxt[u];
             }
         }
     }
@@ -148,7 +176,7 @@ __global__ __launch_bounds__(1024) void tile_kernel(const KernelArgs a)
     // ---- store: one writer per output element
     if (valid) {
         T* __restrict__ y = static_cast<T*>(a.y);
-        const int* __restrict__ kr = a.krow + ((size_t)kb * a.WK + wk) * KW;
+        const SC_CONSTANT int* kr = as_constant(a.krow) + ((size_t)kb * a.WK + wk) * KW;
         const size_t plane = (size_t)a.E * a.F;
         const size_t pix = (size_t)(i0 + i) * a.F + j;
 #pragma unroll
