@@ -104,13 +104,11 @@ int sparse_conv_get_csr(sparse_conv_t h, int* K, long long* nnz,
  * library's counterpart of the per-layer thread-block count the paper tunes
  * (section 8, subBatchSize; section 9).  params[0..nparams) are, in order:
  *   [0] V   images interleaved per LDS element (1, 2, 4 or 8; 0 = automatic)
- *   [1] G   image groups (of V images) per workgroup tile
- *   [2] B   output rows per tile (0 = all rows)
- *   [3] Cc  input channels staged per LDS pass
- *   [4] WP  wavefronts across output positions
- *   [5] WK  wavefronts across output channels
- *   [6] KW  output channels accumulated per wavefront (1, 2, 4, 8 or 16)
- *   [7] LDS budget in bytes per workgroup (0 = default)
+ *   [1] WP  wavefronts across output positions (64 positions each) per workgroup
+ *   [2] WK  wavefronts across output channels per workgroup (WP*WK <= 16)
+ *   [3] KW  output channels accumulated per wavefront (1, 2, 4, 8 or 16)
+ *   [4] Cc  input channels staged per LDS pass
+ *   [5] LDS budget in bytes per workgroup (used when Cc is automatic)
  * Missing trailing entries and zeros mean "automatic".  nparams = 0 restores
  * the automatic choice.  Cached plans are discarded.  SC_EINVAL for values the
  * kernels cannot run; a configuration that cannot fit is reported by forward.
@@ -118,10 +116,10 @@ int sparse_conv_get_csr(sparse_conv_t h, int* K, long long* nnz,
 int sparse_conv_set_launch(sparse_conv_t h, const int* params, int nparams);
 
 /* The launch configuration chosen for a geometry, in the order of
- * sparse_conv_set_launch, followed by [8] workgroups launched, [9] LDS bytes
- * per workgroup, [10] threads per workgroup, [11] stored plan entries
+ * sparse_conv_set_launch, followed by [6] workgroups launched, [7] LDS bytes
+ * per workgroup, [8] threads per workgroup, [9] stored plan entries
  * (including batch padding).  Builds the plan's host side if needed; needs no
- * GPU.  params must have room for 12 ints. */
+ * GPU.  params must have room for 10 ints. */
 int sparse_conv_get_launch(sparse_conv_t h, int N, int H, int W, int stride, int pad, int* params);
 
 /* HIP error code of the last failing runtime call made through this handle (0 if none). */

@@ -126,9 +126,9 @@ def sparse_conv_set_launch(handle: int, params: Sequence[int]) -> None:
 
 
 def sparse_conv_get_launch(handle: int, N: int, H: int, W: int, stride: int, pad: int) -> dict:
-    arr = (C.c_int * 12)()
+    arr = (C.c_int * 10)()
     _check(_lib.sparse_conv_get_launch(handle, N, H, W, stride, pad, arr), "sparse_conv_get_launch", handle)
-    names = ("V", "G", "B", "Cc", "WP", "WK", "KW", "lds_budget", "grid", "lds_bytes", "threads", "entries")
+    names = ("V", "WP", "WK", "KW", "Cc", "lds_budget", "grid", "lds_bytes", "threads", "entries")
     return dict(zip(names, list(arr)))
 
 

@@ -114,19 +114,19 @@ int sparse_conv_get_csr(sparse_conv_t h, int* K, long long* nnz,
 
 int sparse_conv_set_launch(sparse_conv_t h, const int* params, int nparams)
 {
-    if (!h || nparams < 0 || nparams > 8 || (nparams > 0 && !params)) return SC_EINVAL;
-    int v[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    if (!h || nparams < 0 || nparams > 6 || (nparams > 0 && !params)) return SC_EINVAL;
+    int v[6] = {0, 0, 0, 0, 0, 0};
     for (int i = 0; i < nparams; ++i) {
         if (params[i] < 0) return SC_EINVAL;
         v[i] = params[i];
     }
     const int vmax = h->dtype == SC_F16 ? 8 : 4;
     if (v[0] && (v[0] > vmax || (v[0] & (v[0] - 1)))) return SC_EINVAL;
-    if (v[6] && (v[6] > 16 || (v[6] & (v[6] - 1)))) return SC_EINVAL;
-    if (v[4] * (v[5] ? v[5] : 1) > 16 || v[5] > 16) return SC_EINVAL;
-    if (v[7] > 160 * 1024) return SC_EINVAL;
+    if (v[3] && (v[3] > 16 || (v[3] & (v[3] - 1)))) return SC_EINVAL;
+    if (v[1] > 16 || v[2] > 16 || v[1] * (v[2] ? v[2] : 1) > 16) return SC_EINVAL;
+    if (v[5] > 160 * 1024) return SC_EINVAL;
     sc::Launch l;
-    l.V = v[0]; l.G = v[1]; l.B = v[2]; l.Cc = v[3]; l.WP = v[4]; l.WK = v[5]; l.KW = v[6]; l.lds_budget = v[7];
+    l.V = v[0]; l.WP = v[1]; l.WK = v[2]; l.KW = v[3]; l.Cc = v[4]; l.lds_budget = v[5];
     h->over = l;
     h->plans.clear();
     return SC_OK;
@@ -140,8 +140,8 @@ int sparse_conv_get_launch(sparse_conv_t h, int N, int H, int W, int stride, int
         sc::Plan* p = nullptr;
         int rc = sc::get_plan(h, sc::Geometry{N, H, W, stride, pad}, &p);
         if (rc != SC_OK) return rc;
-        const int v[12] = {p->V, p->G, p->B, p->Cc, p->WP, p->WK, p->KW,
-                           h->over.lds_budget, p->grid, p->lds_bytes, p->threads, (int)p->entries.size()};
+        const int v[10] = {p->V, p->WP, p->WK, p->KW, p->Cc, h->over.lds_budget,
+                           p->grid, p->lds_bytes, p->threads, (int)p->entries.size()};
         std::memcpy(params, v, sizeof(v));
         return SC_OK;
     } catch (...) {
@@ -175,11 +175,10 @@ int sparse_conv_forward(sparse_conv_t h, const void* input, void* output,
         a.krow = static_cast<const int*>(p->d_krow);
         a.N = N; a.C = h->C; a.H = H; a.W = W; a.K = h->K; a.E = p->E; a.F = p->F;
         a.stride = stride; a.pad = pad;
-        a.G = p->G; a.B = p->B; a.Cc = p->Cc; a.WP = p->WP; a.WK = p->WK;
-        a.Hb = p->Hb; a.Wp = p->Wp; a.PS = p->PS;
-        a.nchunks = p->nchunks; a.nbands = p->nbands; a.ngroups = p->ngroups;
-        a.ntiles = p->ntiles; a.kblocks = p->kblocks; a.slots = p->slots;
-        a.tile_elems = p->Cc * p->G * p->PS;
+        a.WP = p->WP; a.WK = p->WK; a.Cc = p->Cc;
+        a.Wp = p->Wp; a.Hs = p->Hs; a.Hb = p->Hb; a.CS = p->CS; a.span = p->span;
+        a.nchunks = p->nchunks; a.ngroups = p->ngroups; a.ntiles = p->ntiles; a.kblocks = p->kblocks;
+        a.tile_elems = p->Cc * p->CS;
         const int e = sc::launch_tile_kernel(h->dtype, p->V, p->KW, a, p->grid, p->threads, p->lds_bytes, stream);
         if (e != 0) {
             h->last_hip = e;

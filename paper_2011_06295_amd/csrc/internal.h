@@ -32,12 +32,10 @@ bool encode_csr(const float* w, const unsigned char* mask, int K, int L, bool un
 // Tunables of the tile kernel; 0 = choose automatically.
 struct Launch {
     int V = 0;    // images interleaved per LDS element
-    int G = 0;    // image groups per tile
-    int B = 0;    // output rows per tile
-    int Cc = 0;   // channels per LDS pass
-    int WP = 0;   // wavefronts across positions
+    int WP = 0;   // wavefronts across output positions (64 positions each)
     int WK = 0;   // wavefronts across output channels
     int KW = 0;   // output channels per wavefront
+    int Cc = 0;   // channels per LDS pass
     int lds_budget = 0;
 };
 
@@ -51,27 +49,37 @@ struct Geometry {
 constexpr int kBatch = 8;  // plan entries fetched per scalar load; segments are padded to a multiple
 
 // One stored weight as the kernel consumes it: fp32 weight bits and the LDS
-// element offset (c_local * G * PS + r * Wp + s) of its tap inside the tile.
+// element offset (c_local * CS + r * Wp + s) of its tap relative to a position.
 struct Entry {
     uint32_t wbits;
     int32_t off;
 };
 
 // Everything a forward call needs for one geometry.
+//
+// The batch is laid out (virtually) as one tall zero-padded image per channel:
+// image group g (V images interleaved) occupies rows [g*Hs, (g+1)*Hs) with its
+// `pad` top rows zero, Hs = H + pad; a row holds `pad` zero columns followed by
+// the W real ones, Wp = W + pad.  Bottom and right padding are the next
+// group's top rows and the next row's left columns (Hs and Wp grow by extra
+// zero rows/columns when the padding exceeds the filter, so that every
+// receptive field still starts inside its own group and row).  A position q = Y*Wp + X of
+// that lattice stands for the output whose receptive field starts there; tap
+// (r, s) of it is the element at q + r*Wp + s, so neighbouring lanes always
+// read neighbouring LDS elements, whatever the tap.
 struct Plan {
-    // resolved configuration
-    int V, G, B, Cc, WP, WK, KW;
+    int V, WP, WK, KW, Cc;
     int E, F;
-    int Hb;        // input rows held by a tile: (B-1)*stride + R
-    int Wp;        // tile row pitch in elements: W + 2*pad (at least (F-1)*stride + S)
-    int PS;        // plane stride in elements (one channel of one group)
+    int Wp;        // row pitch of the padded lattice
+    int Hs;        // rows per image group
+    int span;      // positions per workgroup = 64 * WP
+    int Hb;        // lattice rows held by a tile
+    int CS;        // channel stride inside the tile, in elements (= Hb * Wp)
     int nchunks;   // ceil(C / Cc)
-    int nbands;    // ceil(E / B)
     int ngroups;   // ceil(N / V)
-    int ntg;       // ceil(ngroups / G)
-    int ntiles;    // ntg * nbands
+    long long npos;  // positions of the whole batch = ngroups * Hs * Wp
+    int ntiles;    // ceil(npos / span)
     int kblocks;   // ceil(K / (WK*KW))
-    int slots;     // G * B * F output positions per tile
     int threads;   // 64 * WP * WK
     int lds_bytes;
     int grid;      // workgroups launched (tiles rounded up to the XCD count, times kblocks)
@@ -101,9 +109,9 @@ struct KernelArgs {
     const int* seg;
     const int* krow;
     int N, C, H, W, K, E, F, stride, pad;
-    int G, B, Cc, WP, WK, Hb, Wp, PS;
-    int nchunks, nbands, ngroups, ntiles, kblocks, slots;
-    int tile_elems;  // Cc * G * PS
+    int WP, WK, Cc, Wp, Hs, Hb, CS, span;
+    int nchunks, ngroups, ntiles, kblocks;
+    int tile_elems;  // Cc * CS
 };
 
 // Enqueues the tile kernel.  Returns a hipError_t value (0 = success).

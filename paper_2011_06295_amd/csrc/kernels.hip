@@ -5,16 +5,20 @@
 //   Out[n][k][i][j] = sum over stored entries t of row k of
 //                     w[t] * Xpad[n][c_t][i*stride + r_t][j*stride + s_t]
 //
-// Organisation.  A workgroup owns one tile of the input: Cc channels of G image
-// groups (V images interleaved element-wise, so one LDS element is a V-vector
-// and is always naturally aligned whatever the tap shift), Hb rows with halo,
-// zero padding included.  The tile lives in LDS and is reused by every stored
-// weight of every output channel the workgroup handles.  A lane owns one
-// output position (group, row, column); a wavefront owns KW output channels
-// whose accumulators stay in registers across the channel chunks.  Stored
-// weights arrive as (weight, LDS offset) pairs, wave-uniform, fetched in
-// batches of kBatch through the scalar path; per pair a lane does one vector
-// LDS read and V fused multiply-adds in fp32.
+// Organisation.  The batch is seen as one tall zero-padded lattice per channel
+// (image groups of V element-wise interleaved images stacked vertically, each
+// with `pad` zero rows above and `pad` zero columns to the left; see Plan in
+// internal.h).  A workgroup owns `span` consecutive lattice positions and keeps
+// the rows they touch, for Cc channels at a time, in LDS.  A lane owns one
+// position: tap (r, s) of channel c is the LDS element at
+// position + c*CS + r*Wp + s, so the 64 lanes of a wavefront always read 64
+// consecutive, naturally aligned V-vectors (one ds_read_b128 for 4 fp32 or
+// 8 fp16 images), free of bank conflicts whatever the tap.  Positions that fall
+// on padding compute a value nobody stores.  A wavefront owns KW output
+// channels whose accumulators stay in registers across the channel chunks.
+// Stored weights arrive as (weight, LDS offset) pairs, wave-uniform, fetched in
+// batches of kBatch through the scalar path with one batch of look-ahead; per
+// pair a lane does one vector LDS read and V fused multiply-adds in fp32.
 #include <hip/hip_runtime.h>
 
 #include "internal.h"
@@ -65,30 +69,32 @@ __global__ __launch_bounds__(1024) void tile_kernel(const KernelArgs a)
     // tile's input is fetched into a single L2.
     const int bid = blockIdx.x;
     const int xcd = bid & 7;
-    const int q = bid >> 3;
-    const int kb = q % a.kblocks;
-    const int tile_id = (q / a.kblocks) * 8 + xcd;
+    const int qb = bid >> 3;
+    const int kb = qb % a.kblocks;
+    const int tile_id = (qb / a.kblocks) * 8 + xcd;
     if (tile_id >= a.ntiles) return;
-    const int tg = tile_id / a.nbands;
-    const int band = tile_id - tg * a.nbands;
-    const int g0 = tg * a.G;            // first image group of the tile
-    const int i0 = band * a.B;          // first output row of the tile
-    const int y0 = i0 * a.stride - a.pad;  // input row held by tile row 0 (may be negative)
 
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int nwaves = nthreads >> 6;
     const int lane = tid & 63;
     const int wp = wave % a.WP;
     const int wk = wave / a.WP;
 
-    // lane -> output position
-    const int slot = wp * 64 + lane;
-    const int bf = a.B * a.F;
-    const int g = slot / bf;
-    const int rem = slot - g * bf;
-    const int i = rem / a.F;
-    const int j = rem - i * a.F;
-    const bool valid = slot < a.slots && (i0 + i) < a.E && (g0 + g) < a.ngroups;
-    const int base = valid ? g * a.PS + (i * a.stride) * a.Wp + j * a.stride : 0;
+    // The tile covers lattice positions [q0, q0 + span); its row 0 is lattice row Y0.
+    const long long q0 = (long long)tile_id * a.span;
+    const int Y0 = (int)(q0 / a.Wp);
+    const int lq0 = (int)(q0 - (long long)Y0 * a.Wp);
+
+    // lane -> position -> output element (if any)
+    const int lpos = lq0 + wp * 64 + lane;      // tile-local element index of the position
+    const int Yl = lpos / a.Wp;
+    const int X = lpos - Yl * a.Wp;
+    const int Y = Y0 + Yl;
+    const int g = Y / a.Hs;
+    const int yy = Y - g * a.Hs;
+    const int oi = yy / a.stride;
+    const int oj = X / a.stride;
+    const bool valid = g < a.ngroups && oi * a.stride == yy && oj * a.stride == X && oi < a.E && oj < a.F;
 
     float acc[KW][V];
 #pragma unroll
@@ -96,41 +102,48 @@ __global__ __launch_bounds__(1024) void tile_kernel(const KernelArgs a)
 #pragma unroll
         for (int v = 0; v < V; ++v) acc[kk][v] = 0.f;
 
-    // halo, padding and absent images stay zero for the whole kernel
+    // padding rows/columns and absent images stay zero for the whole kernel
     for (int u = tid; u < a.tile_elems; u += nthreads) tile[u] = VT::zero();
 
-    const int ya = y0 > 0 ? y0 : 0;
-    const int yb = (y0 + a.Hb) < a.H ? (y0 + a.Hb) : a.H;
-    const int rows = yb - ya;
     const T* __restrict__ x = static_cast<const T*>(a.x);
-    const size_t img_stride = (size_t)a.C * a.H * a.W;
+    const size_t chan_stride = (size_t)a.H * a.W;
+    const size_t img_stride = (size_t)a.C * chan_stride;
+    const int hbw = a.Hb * a.W;
 
     for (int ch = 0; ch < a.nchunks; ++ch) {
         __syncthreads();  // zero fill done / previous chunk fully consumed
-        // ---- stage the chunk: interior elements only, V images per element
+        // ---- stage the chunk.  A lane owns fixed (row, column) cells of the tile
+        // and walks the channels assigned to its wavefront; consecutive lanes read
+        // consecutive input elements of V images and write one V-vector each.
         const int c0 = ch * a.Cc;
         const int cn = (a.C - c0) < a.Cc ? (a.C - c0) : a.Cc;
-        if (rows > 0) {
-            const int per_c = rows * a.W;
-            const int per_g = cn * per_c;
-            const int total = a.G * per_g;
-            for (int u = tid; u < total; u += nthreads) {
-                const int gg = u / per_g;
-                const int r1 = u - gg * per_g;
-                const int c = r1 / per_c;
-                const int r2 = r1 - c * per_c;
-                const int yy = r2 / a.W;
-                const int xx = r2 - yy * a.W;
-                const int grp = g0 + gg;
-                if (grp >= a.ngroups) continue;
-                const size_t src = ((size_t)(c0 + c) * a.H + (ya + yy)) * a.W + xx;
+        for (int cell = lane; cell < hbw; cell += 64) {
+            const int Yt = cell / a.W;
+            const int xx = cell - Yt * a.W;
+            const int Ys = Y0 + Yt;
+            const int gs = Ys / a.Hs;
+            const int ys = Ys - gs * a.Hs - a.pad;
+            if (gs >= a.ngroups || ys < 0 || ys >= a.H) continue;  // a zero row
+            const int n0 = gs * V;
+            const T* src = x + (size_t)n0 * img_stride + (size_t)c0 * chan_stride + (size_t)ys * a.W + xx;
+            vec* dst = tile + Yt * a.Wp + a.pad + xx;
+            int c = wave;
+            for (; c + 3 * nwaves < cn; c += 4 * nwaves) {
+                vec val[4];
+#pragma unroll
+                for (int t = 0; t < 4; ++t)
+#pragma unroll
+                    for (int v = 0; v < V; ++v)
+                        VT::set(val[t], v, (n0 + v) < a.N ? src[(size_t)v * img_stride + (size_t)(c + t * nwaves) * chan_stride] : T(0));
+#pragma unroll
+                for (int t = 0; t < 4; ++t) dst[(size_t)(c + t * nwaves) * a.CS] = val[t];
+            }
+            for (; c < cn; c += nwaves) {
                 vec val;
 #pragma unroll
-                for (int v = 0; v < V; ++v) {
-                    const int n = grp * V + v;
-                    VT::set(val, v, n < a.N ? x[(size_t)n * img_stride + src] : T(0));
-                }
-                tile[(c * a.G + gg) * a.PS + (ya - y0 + yy) * a.Wp + a.pad + xx] = val;
+                for (int v = 0; v < V; ++v)
+                    VT::set(val, v, (n0 + v) < a.N ? src[(size_t)v * img_stride + (size_t)c * chan_stride] : T(0));
+                dst[(size_t)c * a.CS] = val;
             }
         }
         __syncthreads();
@@ -151,7 +164,7 @@ __global__ __launch_bounds__(1024) void tile_kernel(const KernelArgs a)
             for (int b = 0; b < nb; ++b) {
                 vec xv[kBatch];
 #pragma unroll
-                for (int u = 0; u < kBatch; ++u) xv[u] = tile[base + cur[u].off];
+                for (int u = 0; u < kBatch; ++u) xv[u] = tile[lpos + cur[u].off];
                 e += kBatch;
                 Entry nxt[kBatch];  // look-ahead fetch of the next batch
 #pragma unroll
@@ -178,14 +191,14 @@ __global__ __launch_bounds__(1024) void tile_kernel(const KernelArgs a)
         T* __restrict__ y = static_cast<T*>(a.y);
         const SC_CONSTANT int* kr = as_constant(a.krow) + ((size_t)kb * a.WK + wk) * KW;
         const size_t plane = (size_t)a.E * a.F;
-        const size_t pix = (size_t)(i0 + i) * a.F + j;
+        const size_t pix = (size_t)oi * a.F + oj;
 #pragma unroll
         for (int kk = 0; kk < KW; ++kk) {
             const int k = kr[kk];
             if (k < 0) continue;
 #pragma unroll
             for (int v = 0; v < V; ++v) {
-                const int n = (g0 + g) * V + v;
+                const int n = g * V + v;
                 if (n < a.N) y[((size_t)n * a.K + k) * plane + pix] = (T)acc[kk][v];
             }
         }

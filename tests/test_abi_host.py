@@ -91,8 +91,8 @@ def test_argument_validation_returns_status_codes():
     assert lib.sparse_conv_forward(h, None, None, -1, 8, 8, 1, 1, None) == B.SC_EINVAL
     assert lib.sparse_conv_forward(None, None, None, 1, 8, 8, 1, 1, None) == B.SC_EINVAL
     assert lib.sparse_conv_forward(h, None, None, 0, 8, 8, 1, 1, None) == B.SC_OK               # empty batch: no-op
-    bad = (C.c_int * 8)(3, 0, 0, 0, 0, 0, 0, 0)
-    assert lib.sparse_conv_set_launch(h, bad, 8) == B.SC_EINVAL                                  # V must be a power of two
+    bad = (C.c_int * 6)(3, 0, 0, 0, 0, 0)
+    assert lib.sparse_conv_set_launch(h, bad, 6) == B.SC_EINVAL                                  # V must be a power of two
     assert lib.sparse_conv_strerror(B.SC_EINVAL) == b"invalid argument"
     lib.sparse_conv_destroy(h)
     lib.sparse_conv_destroy(None)

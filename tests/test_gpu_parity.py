@@ -72,13 +72,15 @@ def test_random_small_layers(shape, dtype):
 
 
 LAUNCHES = [
-    # V, G, B, Cc, WP, WK, KW, lds
-    [1, 1, 0, 0, 0, 1, 1, 0],
-    [1, 2, 3, 2, 0, 2, 2, 0],
-    [2, 3, 2, 5, 0, 4, 4, 0],
-    [4, 2, 0, 3, 0, 2, 16, 0],
-    [4, 1, 5, 16, 0, 1, 8, 0],
-    [2, 4, 4, 1, 0, 3, 2, 0],
+    # V, WP, WK, KW, Cc, lds budget
+    [1, 1, 1, 1, 0, 0],
+    [1, 2, 2, 2, 2, 0],
+    [2, 1, 4, 4, 5, 0],
+    [4, 2, 2, 16, 3, 0],
+    [4, 1, 1, 8, 16, 0],
+    [2, 3, 3, 2, 1, 0],
+    [4, 4, 4, 1, 0, 40960],
+    [0, 8, 2, 2, 7, 0],
 ]
 
 
