@@ -1,6 +1,7 @@
 // C ABI of libsparseconv (declared in include/sparse_conv.h).
 #include <hip/hip_runtime_api.h>
 
+#include <algorithm>
 #include <cstring>
 #include <new>
 
@@ -156,11 +157,13 @@ int sparse_conv_forward(sparse_conv_t h, const void* input, void* output,
     if (!sc::geometry_ok(h, H, W, stride, pad)) return SC_EINVAL;
     if (N == 0) return SC_OK;
     if (!input || !output || input == output) return SC_EINVAL;
-    if ((long long)N * h->K * (long long)H * W > (1ll << 40)) return SC_EINVAL;
     try {
         sc::Plan* p = nullptr;
         int rc = sc::get_plan(h, sc::Geometry{N, H, W, stride, pad}, &p);
         if (rc != SC_OK) return rc;
+        // the kernels index both tensors with 32-bit element offsets
+        if ((long long)N * h->C * H * W >= (1ll << 31) || (long long)N * h->K * p->E * p->F >= (1ll << 31))
+            return SC_EUNSUPPORTED;
         if (!p->uploaded) {
             if ((rc = sc::upload(h, p->entries, &p->d_entries)) != SC_OK) return rc;
             if ((rc = sc::upload(h, p->seg, &p->d_seg)) != SC_OK) return rc;
@@ -179,6 +182,12 @@ int sparse_conv_forward(sparse_conv_t h, const void* input, void* output,
         a.Wp = p->Wp; a.Hs = p->Hs; a.Hb = p->Hb; a.CS = p->CS; a.span = p->span;
         a.nchunks = p->nchunks; a.ngroups = p->ngroups; a.ntiles = p->ntiles; a.kblocks = p->kblocks;
         a.tile_elems = p->Cc * p->CS;
+        a.RW = std::min(H, p->Hb);
+        a.fd_Wp = sc::make_fastdiv(p->Wp);
+        a.fd_Hs = sc::make_fastdiv(p->Hs);
+        a.fd_W = sc::make_fastdiv(W);
+        a.fd_chan = sc::make_fastdiv(a.RW * W);
+        a.fd_group = sc::make_fastdiv(p->Cc * a.RW * W);
         const int e = sc::launch_tile_kernel(h->dtype, p->V, p->KW, a, p->grid, p->threads, p->lds_bytes, stream);
         if (e != 0) {
             h->last_hip = e;

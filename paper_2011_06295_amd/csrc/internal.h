@@ -49,7 +49,8 @@ struct Geometry {
 constexpr int kBatch = 8;  // plan entries fetched per scalar load; segments are padded to a multiple
 
 // One stored weight as the kernel consumes it: fp32 weight bits and the LDS
-// element offset (c_local * CS + r * Wp + s) of its tap relative to a position.
+// byte offset ((c_local * CS + r * Wp + s) * element bytes) of its tap relative
+// to a position.
 struct Entry {
     uint32_t wbits;
     int32_t off;
@@ -85,7 +86,7 @@ struct Plan {
     int grid;      // workgroups launched (tiles rounded up to the XCD count, times kblocks)
     // host tables
     std::vector<Entry> entries;   // segments padded to kBatch
-    std::vector<int> seg;         // [kblocks][nchunks][WK][KW][2] = (first entry, batches)
+    std::vector<int> seg;         // [kblocks][nchunks][WK][1 + KW] = first entry, batches of each row
     std::vector<int> krow;        // [kblocks][WK][KW] output channel or -1
     // device copies (owned)
     void* d_entries = nullptr;
@@ -102,6 +103,12 @@ int build_plan(const Csr& csr, int C, int R, int S, int elem_bytes, const Geomet
 
 // ---------------------------------------------------------------- kernels
 
+// Division by a run-time constant: q = n / d for 0 <= n < 2^31.
+struct FastDiv {
+    uint32_t mul, shift, d;
+};
+FastDiv make_fastdiv(int d);
+
 struct KernelArgs {
     const void* x;
     void* y;
@@ -112,6 +119,8 @@ struct KernelArgs {
     int WP, WK, Cc, Wp, Hs, Hb, CS, span;
     int nchunks, ngroups, ntiles, kblocks;
     int tile_elems;  // Cc * CS
+    int RW;          // row slots per (group, channel) in the staging map: min(H, Hb)
+    FastDiv fd_Wp, fd_Hs, fd_W, fd_chan, fd_group;  // divisors Wp, Hs, W, RW*W, Cc*RW*W
 };
 
 // Enqueues the tile kernel.  Returns a hipError_t value (0 = success).

@@ -25,6 +25,8 @@
 
 namespace sc {
 
+constexpr int kStage = 4;  // tile elements a thread stages per round (loads in flight: kStage * V)
+
 // Read-only plan tables are addressed through the constant address space: a
 // wave-uniform load from it is always issued on the scalar path (s_load), which
 // an ordinary global pointer loses once a barrier sits between store and load.
@@ -37,6 +39,12 @@ __device__ __forceinline__ const SC_CONSTANT T* as_constant(const T* p)
     return (const SC_CONSTANT T*)(p);
 }
 #pragma clang diagnostic pop
+
+// n / d for 0 <= n < 2^31 with the multiplier prepared on the host.
+__device__ __forceinline__ int fdiv(int n, const FastDiv& f)
+{
+    return f.d == 1 ? n : (int)(__umulhi((unsigned)n, f.mul) >> f.shift);
+}
 
 template <typename T, int V>
 struct Vec {
@@ -65,32 +73,33 @@ __global__ __launch_bounds__(1024) void tile_kernel(const KernelArgs a)
     const int nthreads = blockDim.x;
 
     // Workgroup -> (tile, channel block).  Consecutive workgroup ids go round
-    // the 8 XCDs; all channel blocks of one tile are kept on one XCD so the
-    // tile's input is fetched into a single L2.
+    // the 8 XCDs.  Each XCD gets one contiguous range of tiles and all their
+    // channel blocks, so a tile's rows, which its neighbours and its other
+    // channel blocks stage again, are fetched into a single L2.
     const int bid = blockIdx.x;
     const int xcd = bid & 7;
     const int qb = bid >> 3;
     const int kb = qb % a.kblocks;
-    const int tile_id = (qb / a.kblocks) * 8 + xcd;
-    if (tile_id >= a.ntiles) return;
+    const int tile_id = xcd * ((a.ntiles + 7) >> 3) + qb / a.kblocks;
+    if (tile_id >= a.ntiles || qb / a.kblocks >= ((a.ntiles + 7) >> 3)) return;
 
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int nwaves = nthreads >> 6;
     const int lane = tid & 63;
     const int wp = wave % a.WP;
     const int wk = wave / a.WP;
 
     // The tile covers lattice positions [q0, q0 + span); its row 0 is lattice row Y0.
     const long long q0 = (long long)tile_id * a.span;
-    const int Y0 = (int)(q0 / a.Wp);
-    const int lq0 = (int)(q0 - (long long)Y0 * a.Wp);
+    const int Y0 = fdiv((int)q0, a.fd_Wp);      // the host guarantees fewer than 2^31 positions
+    const int lq0 = (int)q0 - Y0 * a.Wp;
 
     // lane -> position -> output element (if any)
     const int lpos = lq0 + wp * 64 + lane;      // tile-local element index of the position
-    const int Yl = lpos / a.Wp;
+    const int lposb = lpos * (int)sizeof(vec);
+    const int Yl = fdiv(lpos, a.fd_Wp);
     const int X = lpos - Yl * a.Wp;
     const int Y = Y0 + Yl;
-    const int g = Y / a.Hs;
+    const int g = fdiv(Y, a.fd_Hs);
     const int yy = Y - g * a.Hs;
     const int oi = yy / a.stride;
     const int oj = X / a.stride;
@@ -106,67 +115,110 @@ __global__ __launch_bounds__(1024) void tile_kernel(const KernelArgs a)
     for (int u = tid; u < a.tile_elems; u += nthreads) tile[u] = VT::zero();
 
     const T* __restrict__ x = static_cast<const T*>(a.x);
-    const size_t chan_stride = (size_t)a.H * a.W;
-    const size_t img_stride = (size_t)a.C * chan_stride;
-    const int hbw = a.Hb * a.W;
+    const int chan_stride = a.H * a.W;
+    const int img_stride = a.C * chan_stride;   // the host guarantees N*C*H*W < 2^31
+
+    // Staging map.  The tile's real (non-padding) elements are enumerated group
+    // by group, inside a group channel by channel, inside a channel row by row
+    // (RW row slots per channel, RW = min(H, Hb)): in that order one image's
+    // elements are contiguous in memory across rows and channels, so consecutive
+    // lanes load consecutive addresses even when a feature map is only a few
+    // pixels large.  Slots whose row lies outside the tile are skipped.  Thread `tid` owns elements tid,
+    // tid + nthreads, ...  Decoding an element gives:
+    //   src  input element offset of image 0 of the group at chunk channel 0, or -1 for none
+    //   dc   tile element index | channel << 17 | (valid images - 1) << 28
+    const int g_first = fdiv(Y0, a.fd_Hs);
+    const int g_count = fdiv(Y0 + a.Hb - 1, a.fd_Hs) - g_first + 1;
+    const int chan_slots = a.RW * a.W;          // a group holds at most RW rows of the tile
+    const int group_slots = a.Cc * chan_slots;
+    const int units = g_count * group_slots;    // enumerated slots of a full chunk (some fall outside the tile)
+    auto decode = [&](int u, int& src, int& dc) {
+        const int gi = fdiv(u, a.fd_group);
+        const int rem = u - gi * group_slots;
+        const int c = fdiv(rem, a.fd_chan);
+        const int r2 = rem - c * chan_slots;
+        const int yr = fdiv(r2, a.fd_W);
+        const int xx = r2 - yr * a.W;
+        const int gs = g_first + gi;
+        int r_lo = Y0 - gs * a.Hs - a.pad;      // first input row of group gs inside the tile
+        int r_hi = r_lo + a.Hb;
+        if (r_lo < 0) r_lo = 0;
+        if (r_hi > a.H) r_hi = a.H;
+        const int ys = r_lo + yr;
+        const int Yt = gs * a.Hs + a.pad + ys - Y0;
+        const int left = a.N - gs * V;
+        const int nv = left < V ? left : V;
+        const bool ok = u < units && gs < a.ngroups && ys < r_hi;
+        src = ok ? gs * V * img_stride + c * chan_stride + ys * a.W + xx : -1;
+        dc = ok ? ((c * a.CS + Yt * a.Wp + a.pad + xx) | (c << 17) | ((nv - 1) << 28)) : 0;
+    };
+    const int round_units = kStage * nthreads;
+
+    // Per (channel block, chunk, wavefront) descriptor: first plan entry, then the
+    // batch count of each of the KW rows; the KW segments are contiguous in the
+    // entry table.  The descriptor of the next chunk and the first batch of this
+    // chunk are requested before staging starts, so their latency is hidden.
+    const SC_CONSTANT int* sg = as_constant(a.seg) + ((size_t)kb * a.nchunks * a.WK + wk) * (KW + 1);
+    const size_t sg_step = (size_t)a.WK * (KW + 1);
+    int d_start = sg[0];
+    int d_nb[KW];
+#pragma unroll
+    for (int kk = 0; kk < KW; ++kk) d_nb[kk] = sg[1 + kk];
 
     for (int ch = 0; ch < a.nchunks; ++ch) {
+        const SC_CONSTANT Entry* e = as_constant(a.entries) + d_start;
+        int nb[KW];
+#pragma unroll
+        for (int kk = 0; kk < KW; ++kk) nb[kk] = d_nb[kk];
+        Entry cur[kBatch];
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u) {  // the table ends in kBatch slack entries
+            cur[u].wbits = e[u].wbits;
+            cur[u].off = e[u].off;
+        }
+        if (ch + 1 < a.nchunks) {
+            sg += sg_step;
+            d_start = sg[0];
+#pragma unroll
+            for (int kk = 0; kk < KW; ++kk) d_nb[kk] = sg[1 + kk];
+        }
+
         __syncthreads();  // zero fill done / previous chunk fully consumed
-        // ---- stage the chunk.  A lane owns fixed (row, column) cells of the tile
-        // and walks the channels assigned to its wavefront; consecutive lanes read
-        // consecutive input elements of V images and write one V-vector each.
+        // ---- stage the chunk: all loads of a round are issued before the first LDS write
         const int c0 = ch * a.Cc;
         const int cn = (a.C - c0) < a.Cc ? (a.C - c0) : a.Cc;
-        for (int cell = lane; cell < hbw; cell += 64) {
-            const int Yt = cell / a.W;
-            const int xx = cell - Yt * a.W;
-            const int Ys = Y0 + Yt;
-            const int gs = Ys / a.Hs;
-            const int ys = Ys - gs * a.Hs - a.pad;
-            if (gs >= a.ngroups || ys < 0 || ys >= a.H) continue;  // a zero row
-            const int n0 = gs * V;
-            const T* src = x + (size_t)n0 * img_stride + (size_t)c0 * chan_stride + (size_t)ys * a.W + xx;
-            vec* dst = tile + Yt * a.Wp + a.pad + xx;
-            int c = wave;
-            for (; c + 3 * nwaves < cn; c += 4 * nwaves) {
-                vec val[4];
+        const T* __restrict__ xc = x + (size_t)c0 * chan_stride;
+        for (int r0 = 0; r0 < units; r0 += round_units) {
+            int src[kStage], dc[kStage];
 #pragma unroll
-                for (int t = 0; t < 4; ++t)
-#pragma unroll
-                    for (int v = 0; v < V; ++v)
-                        VT::set(val[t], v, (n0 + v) < a.N ? src[(size_t)v * img_stride + (size_t)(c + t * nwaves) * chan_stride] : T(0));
-#pragma unroll
-                for (int t = 0; t < 4; ++t) dst[(size_t)(c + t * nwaves) * a.CS] = val[t];
+            for (int t = 0; t < kStage; ++t) {
+                decode(r0 + tid + t * nthreads, src[t], dc[t]);
+                if (((dc[t] >> 17) & 0x7ff) >= cn) src[t] = -1;
             }
-            for (; c < cn; c += nwaves) {
-                vec val;
+            vec val[kStage];
+#pragma unroll
+            for (int t = 0; t < kStage; ++t) {
+                const int nv = ((dc[t] >> 28) & 7) + 1;
 #pragma unroll
                 for (int v = 0; v < V; ++v)
-                    VT::set(val, v, (n0 + v) < a.N ? src[(size_t)v * img_stride + (size_t)c * chan_stride] : T(0));
-                dst[(size_t)c * a.CS] = val;
+                    VT::set(val[t], v, (src[t] >= 0 && v < nv) ? xc[(size_t)src[t] + (size_t)v * img_stride] : T(0));
             }
+#pragma unroll
+            for (int t = 0; t < kStage; ++t)
+                if (src[t] >= 0) tile[dc[t] & 0x1ffff] = val[t];
         }
         __syncthreads();
 
         // ---- gather-FMA over this wavefront's KW rows
-        const SC_CONSTANT int* sg = as_constant(a.seg) + (((size_t)kb * a.nchunks + ch) * a.WK + wk) * (KW * 2);
 #pragma unroll
         for (int kk = 0; kk < KW; ++kk) {
-            const int start = sg[2 * kk];
-            const int nb = sg[2 * kk + 1];
-            const SC_CONSTANT Entry* e = as_constant(a.entries) + start;
-            Entry cur[kBatch];
-#pragma unroll
-            for (int u = 0; u < kBatch; ++u) {  // the table ends in kBatch slack entries
-                cur[u].wbits = e[u].wbits;
-                cur[u].off = e[u].off;
-            }
-            for (int b = 0; b < nb; ++b) {
+            for (int b = 0; b < nb[kk]; ++b) {
                 vec xv[kBatch];
 #pragma unroll
-                for (int u = 0; u < kBatch; ++u) xv[u] = tile[lpos + cur[u].off];
+                for (int u = 0; u < kBatch; ++u)  // entry offsets are in bytes: one VOP2 add per read
+                    xv[u] = *reinterpret_cast<const vec*>(smem + (lposb + cur[u].off));
                 e += kBatch;
-                Entry nxt[kBatch];  // look-ahead fetch of the next batch
+                Entry nxt[kBatch];  // look-ahead fetch of the next batch (possibly the next row's first)
 #pragma unroll
                 for (int u = 0; u < kBatch; ++u) {
                     nxt[u].wbits = e[u].wbits;

@@ -77,6 +77,19 @@ double estimate(const Shape& s, const Cand& c)
 
 }  // namespace
 
+// floor(n / d) = (n * mul) >> (32 + shift) for every 0 <= n < 2^31, where
+// mul = floor(2^(31+s) / d) + 1 and shift = s - 1 with 2^(s-1) < d <= 2^s.
+FastDiv make_fastdiv(int d)
+{
+    FastDiv f{0u, 0u, (uint32_t)d};
+    if (d <= 1) return f;
+    int s = 0;
+    while ((1ll << s) < d) ++s;
+    f.mul = (uint32_t)((1ull << (31 + s)) / (uint64_t)d + 1ull);
+    f.shift = (uint32_t)(s - 1);
+    return f;
+}
+
 int build_plan(const Csr& csr, int C, int R, int S, int elem_bytes, const Geometry& g,
                const Launch& over, Plan& p)
 {
@@ -106,7 +119,7 @@ int build_plan(const Csr& csr, int C, int R, int S, int elem_bytes, const Geomet
     const int ngroups = std::max(1, cdiv(g.N, V));
     s.npos = (long long)ngroups * s.Hs * s.Wp;
     s.row_nnz = K > 0 ? (double)csr.colidx.size() / K : 0.0;
-    if (s.npos > (1ll << 40)) return SC_EUNSUPPORTED;
+    if (s.npos + 1024 >= (1ll << 31)) return SC_EUNSUPPORTED;  // positions are 32-bit in the kernel
 
     if (over.lds_budget > kMaxLds) return SC_EINVAL;
     if (over.KW && !pow2_in(over.KW, 1, 16)) return SC_EINVAL;
@@ -135,6 +148,7 @@ int build_plan(const Csr& csr, int C, int R, int S, int elem_bytes, const Geomet
                     const int budget = over.lds_budget ? over.lds_budget : budgets[bi];
                     int Cc = over.Cc ? std::min(over.Cc, C) : (int)std::min<long long>(C, budget / (CS * s.ub));
                     if (Cc < 1) continue;
+                    Cc = std::min(Cc, 2047);                     // the staging map keeps the channel in 11 bits
                     if (!over.Cc) Cc = cdiv(C, cdiv(C, Cc));     // even chunks
                     const long long lds = (long long)Cc * CS * s.ub;
                     if (lds > kMaxLds) continue;
@@ -173,38 +187,41 @@ int build_plan(const Csr& csr, int C, int R, int S, int elem_bytes, const Geomet
 
     const int RS = R * S;
     const int nchunks = p.nchunks;
-    p.seg.assign((size_t)p.kblocks * nchunks * KB * 2, 0);
+    const int SW = p.KW + 1;  // descriptor: first entry, then batches of each of the KW rows
+    p.seg.assign((size_t)p.kblocks * nchunks * p.WK * SW, 0);
     p.entries.clear();
     for (int kb = 0; kb < p.kblocks; ++kb)
         for (int ch = 0; ch < nchunks; ++ch) {
             const int c0 = ch * p.Cc, c1 = std::min(C, c0 + p.Cc);
-            for (int w = 0; w < KB; ++w) {
-                const int k = p.krow[(size_t)kb * KB + w];
-                int* sg = &p.seg[(((size_t)kb * nchunks + ch) * KB + w) * 2];
+            for (int wk = 0; wk < p.WK; ++wk) {
+                int* sg = &p.seg[(((size_t)kb * nchunks + ch) * p.WK + wk) * SW];
                 sg[0] = (int)p.entries.size();
-                sg[1] = 0;
-                if (k < 0) continue;
-                const int* cb = csr.colidx.data() + csr.rowptr[k];
-                const int* ce = csr.colidx.data() + csr.rowptr[k + 1];
-                const int* lo = std::lower_bound(cb, ce, c0 * RS);
-                const int* hi = std::lower_bound(cb, ce, c1 * RS);
-                const int n = (int)(hi - lo);
-                if (n == 0) continue;
-                Entry last{0u, 0};
-                for (const int* q = lo; q < hi; ++q) {
-                    const int col = *q;
-                    const int c = col / RS, r = (col / S) % R, sx = col % S;
-                    const float wv = csr.val32[(size_t)(q - csr.colidx.data())];
-                    uint32_t wb;
-                    __builtin_memcpy(&wb, &wv, 4);
-                    last = Entry{wb, (c - c0) * p.CS + r * p.Wp + sx};
-                    p.entries.push_back(last);
+                for (int kk = 0; kk < p.KW; ++kk) {
+                    const int k = p.krow[(size_t)kb * KB + wk * p.KW + kk];
+                    sg[1 + kk] = 0;
+                    if (k < 0) continue;
+                    const int* cb = csr.colidx.data() + csr.rowptr[k];
+                    const int* ce = csr.colidx.data() + csr.rowptr[k + 1];
+                    const int* lo = std::lower_bound(cb, ce, c0 * RS);
+                    const int* hi = std::lower_bound(cb, ce, c1 * RS);
+                    const int n = (int)(hi - lo);
+                    if (n == 0) continue;
+                    Entry last{0u, 0};
+                    for (const int* q = lo; q < hi; ++q) {
+                        const int col = *q;
+                        const int c = col / RS, r = (col / S) % R, sx = col % S;
+                        const float wv = csr.val32[(size_t)(q - csr.colidx.data())];
+                        uint32_t wb;
+                        __builtin_memcpy(&wb, &wv, 4);
+                        last = Entry{wb, ((c - c0) * p.CS + r * p.Wp + sx) * s.ub};
+                        p.entries.push_back(last);
+                    }
+                    const int nb = cdiv(n, kBatch);
+                    // padding repeats the last real tap with weight zero
+                    for (int t = n; t < nb * kBatch; ++t) p.entries.push_back(Entry{0u, last.off});
+                    sg[1 + kk] = nb;
+                    if (p.entries.size() > (size_t)INT_MAX / 2) return SC_EUNSUPPORTED;
                 }
-                const int nb = cdiv(n, kBatch);
-                // padding repeats the last real tap with weight zero
-                for (int t = n; t < nb * kBatch; ++t) p.entries.push_back(Entry{0u, last.off});
-                sg[1] = nb;
-                if (p.entries.size() > (size_t)INT_MAX / 2) return SC_EUNSUPPORTED;
             }
         }
     for (int t = 0; t < kBatch; ++t) p.entries.push_back(Entry{0u, 0});  // slack for look-ahead fetches
