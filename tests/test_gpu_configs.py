@@ -1,0 +1,144 @@
+"""GPU parity on the five benchmark configurations, in the launch configuration
+bench.py times.  Small cases are compared element by element; at full batch
+size the oracle evaluates sampled output coordinates one by one (exact-order
+double sums of the same operands the GPU layer received)."""
+import numpy as np
+import pytest
+
+import oracle
+from helpers import TOL, assert_close
+
+pytestmark = pytest.mark.gpu
+
+
+def _net(work, layer_ids=None):
+    from paper_2011_06295_amd import harness
+    return harness.Network(work, layer_ids=layer_ids)
+
+
+def _oracle_operands(w, m, x, dtype):
+    rowptr, colidx, values = oracle.csr_encode(w, m)
+    if dtype == "f16":
+        values = oracle.round_through_f16(values)
+        x = oracle.round_through_f16(x)
+    return (rowptr, colidx, values), x
+
+
+def check_layer_full(run, wm, dtype, what):
+    """Whole output of one layer against the oracle fed with the layer's own device input."""
+    import torch
+    w, m = wm
+    s = run.spec
+    x = run.x.float().cpu().numpy()
+    csr, xo = _oracle_operands(w, m, x, dtype)
+    ref = oracle.sparse_conv(csr, xo, s.K, s.R, s.S, s.stride, s.pad)
+    got = run.y.float().cpu().numpy()
+    return assert_close(got, ref, TOL[dtype], what)
+
+
+def check_layer_sampled(run, wm, dtype, what, npts=3000, seed=0):
+    """Sampled output coordinates at full size; tolerance scale from the sampled references."""
+    w, m = wm
+    s = run.spec
+    x = run.x.float().cpu().numpy()
+    N = x.shape[0]
+    rng = np.random.default_rng(seed)
+    pts = np.stack([rng.integers(0, N, npts), rng.integers(0, s.K, npts),
+                    rng.integers(0, s.E, npts), rng.integers(0, s.F, npts)], 1).astype(np.int32)
+    # always include the corners of the index space (first/last image, channel, pixel)
+    corners = np.array([[n, k, i, j] for n in (0, N - 1) for k in (0, s.K - 1)
+                        for i in (0, s.E - 1) for j in (0, s.F - 1)], dtype=np.int32)
+    pts = np.concatenate([corners, pts])
+    csr, xo = _oracle_operands(w, m, x, dtype)
+    ref = oracle.sparse_conv_points(csr, xo, s.K, s.R, s.S, s.stride, s.pad, pts)
+    y = run.y.float().cpu().numpy()
+    got = y[pts[:, 0], pts[:, 1], pts[:, 2], pts[:, 3]]
+    return assert_close(got, ref, TOL[dtype], what)
+
+
+def test_config2_lenet_chain_full():
+    from paper_2011_06295_amd import workloads as wl
+    work = wl.lenet5(64)
+    net = _net(work)
+    x0 = wl.make_input(work)
+    net.run_chain(x0)
+    for li, run in enumerate(net.runs):
+        print("lenet", run.spec.name, run.layer.get_launch(work.N, run.spec.H, run.spec.W, run.spec.stride, run.spec.pad), flush=True)
+        check_layer_full(run, net.host_weights[li], "f32", f"lenet-{run.spec.name}")
+    # the oracle's own chain (its ReLU and max-pool) from the same input
+    a = x0
+    for li, run in enumerate(net.runs):
+        w, m = net.host_weights[li]
+        s = run.spec
+        y = oracle.sparse_conv(oracle.csr_encode(w, m), a, s.K, s.R, s.S, s.stride, s.pad)
+        assert_close(run.y.float().cpu().numpy(), y, 5e-5, f"lenet-chain-{s.name}")
+        if s.pool_after and s.pool_before_relu:
+            y = oracle.maxpool2(y)
+        if s.relu_after:
+            y = oracle.relu(y)
+        if s.pool_after and not s.pool_before_relu:
+            y = oracle.maxpool2(y)
+        a = y
+    net.close()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+def test_vgg_small_batch_every_element(dtype):
+    """All 13 layers at batch 6 (one full and one partial image group), every output element."""
+    from paper_2011_06295_amd import workloads as wl
+    work = wl.vgg16(6, dtype)
+    net = _net(work)
+    net.run_chain(wl.make_input(work))
+    for li, run in enumerate(net.runs):
+        err = check_layer_full(run, net.host_weights[li], dtype, f"vgg6-{dtype}-{run.spec.name}")
+        print(f"vgg batch 6 {dtype} {run.spec.name}: max err / max|ref| = {err:.3g}", flush=True)
+    net.close()
+
+
+@pytest.mark.parametrize("dtype,N", [("f32", 128), ("f16", 256)])
+def test_config3_4_vgg_full_batch_sampled(dtype, N):
+    from paper_2011_06295_amd import workloads as wl
+    work = wl.vgg16(N, dtype)
+    net = _net(work)
+    out = net.run_chain(wl.make_input(work))
+    assert np.isfinite(out.float().cpu().numpy()).all()
+    for li, run in enumerate(net.runs):
+        err = check_layer_sampled(run, net.host_weights[li], dtype, f"vgg{N}-{dtype}-{run.spec.name}", seed=li)
+        print(f"vgg batch {N} {dtype} {run.spec.name}: max err / max|ref| = {err:.3g}", flush=True)
+    net.close()
+
+
+@pytest.mark.parametrize("ragged", [False, True], ids=["unified", "ragged"])
+@pytest.mark.parametrize("sparsity_bp", [5000, 7000, 8000, 9000, 9500, 9900])
+def test_config5_sweep_sampled(sparsity_bp, ragged):
+    from paper_2011_06295_amd import workloads as wl
+    work = wl.sweep_layer(sparsity_bp, ragged, 256)
+    net = _net(work, layer_ids=[wl.sweep_layer_index(sparsity_bp, ragged)])
+    net.run_chain(wl.make_input(work))
+    run = net.runs[0]
+    err = check_layer_sampled(run, net.host_weights[0], "f32", f"sweep-{sparsity_bp}-{ragged}", npts=2000, seed=sparsity_bp)
+    print(f"sweep {sparsity_bp} ragged={ragged}: nnz {run.nnz} max err / max|ref| = {err:.3g}", flush=True)
+    net.close()
+
+
+def test_config5_unify_flag_matches_plain_rows():
+    """Ragged rows padded to a unified count with explicit zeros give the same numbers."""
+    import torch
+    from paper_2011_06295_amd import binding as B, workloads as wl
+    work = wl.sweep_layer(9000, True, 8)
+    spec = work.layers[0]
+    lid = wl.sweep_layer_index(9000, True)
+    w, m = wl.make_weights(5, lid, spec), wl.make_mask(5, lid, spec)
+    x = torch.from_numpy(wl.make_input(work)).cuda()
+    plain = B.SparseConv(w, m, "f32", unify=False)
+    unified = B.SparseConv(w, m, "f32", unify=True)
+    rp = unified.csr()[0]
+    assert len(set(np.diff(rp).tolist())) == 1
+    ya = plain.forward(x, 1, 1).cpu().numpy()
+    yb = unified.forward(x, 1, 1).cpu().numpy()
+    assert_close(yb, ya, 1e-6, "unify-vs-plain")
+    csr = oracle.csr_encode(w, m)
+    ref = oracle.sparse_conv(csr, x.cpu().numpy(), spec.K, 3, 3, 1, 1)
+    assert_close(ya, ref, TOL["f32"], "sweep-ragged-full")
+    plain.close()
+    unified.close()
