@@ -17,7 +17,9 @@ SC_OK, SC_EINVAL, SC_EUNSUPPORTED, SC_ENOMEM, SC_EHIP = 0, -1, -2, -3, -4
 SC_F32, SC_F16 = 0, 1
 SC_FLAG_UNIFY_NNZ = 1
 
-LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libsparseconv.so")
+# SPARSECONV_LIBRARY names another build of the same library (e.g. an instrumented one)
+LIB_PATH = os.environ.get("SPARSECONV_LIBRARY") or os.path.join(
+    os.path.dirname(os.path.abspath(__file__)), "libsparseconv.so")
 
 EXPORTS = (
     "sparse_conv_create", "sparse_conv_output_shape", "sparse_conv_forward",

@@ -8,6 +8,15 @@
 #include "../../include/sparse_conv.h"
 #include "internal.h"
 
+#ifdef SC_PHASE_TIMING
+// developer instrumentation: device buffer of 8 counters per workgroup (see kernels.hip)
+static unsigned long long* g_phase_buffer = nullptr;
+extern "C" void sparse_conv_debug_phase_buffer(void* device_buffer)
+{
+    g_phase_buffer = static_cast<unsigned long long*>(device_buffer);
+}
+#endif
+
 namespace sc {
 
 Plan::~Plan()
@@ -182,12 +191,27 @@ int sparse_conv_forward(sparse_conv_t h, const void* input, void* output,
         a.Wp = p->Wp; a.Hs = p->Hs; a.Hb = p->Hb; a.CS = p->CS; a.span = p->span;
         a.nchunks = p->nchunks; a.ngroups = p->ngroups; a.ntiles = p->ntiles; a.kblocks = p->kblocks;
         a.tile_elems = p->Cc * p->CS;
-        a.RW = std::min(H, p->Hb);
+        a.SL = p->SL; a.rows_mode = p->rows_mode; a.tbl_off = p->tbl_off;
+        a.SG = p->SG; a.SP = p->SP;
+        a.nbuf = p->nbuf;
+        a.npass = (int)(((long long)p->SG * p->Cc * p->SP + (long long)sc::kStage * p->threads - 1) /
+                        ((long long)sc::kStage * p->threads));
+        {
+            const long long CP = (long long)p->Cc * p->SP;   // < 2^31: Cc * SP elements fit in LDS
+            a.st_dg = (int)(p->threads / CP);
+            const int r = (int)(p->threads % CP);
+            a.st_dc = r / p->SP;
+            a.st_dp = r % p->SP;
+            a.fd_CP = sc::make_fastdiv((int)CP);
+        }
         a.fd_Wp = sc::make_fastdiv(p->Wp);
         a.fd_Hs = sc::make_fastdiv(p->Hs);
         a.fd_W = sc::make_fastdiv(W);
-        a.fd_chan = sc::make_fastdiv(a.RW * W);
-        a.fd_group = sc::make_fastdiv(p->Cc * a.RW * W);
+        a.fd_HW = sc::make_fastdiv(H * W);
+        a.fd_SP = sc::make_fastdiv(p->SP);
+#ifdef SC_PHASE_TIMING
+        a.phase = g_phase_buffer;
+#endif
         const int e = sc::launch_tile_kernel(h->dtype, p->V, p->KW, a, p->grid, p->threads, p->lds_bytes, stream);
         if (e != 0) {
             h->last_hip = e;

@@ -46,6 +46,7 @@ struct Geometry {
     }
 };
 
+constexpr int kStage = 4;  // tile elements a thread stages per chunk (loads in flight: kStage * V)
 constexpr int kBatch = 8;  // plan entries fetched per scalar load; segments are padded to a multiple
 
 // One stored weight as the kernel consumes it: fp32 weight bits and the LDS
@@ -82,8 +83,13 @@ struct Plan {
     int ntiles;    // ceil(npos / span)
     int kblocks;   // ceil(K / (WK*KW))
     int threads;   // 64 * WP * WK
-    int lds_bytes;
-    int grid;      // workgroups launched (tiles rounded up to the XCD count, times kblocks)
+    int nbuf;      // tile buffers in LDS: 2 when there are several chunks
+    int SL;        // staging slots per channel = SG * SP
+    int SG, SP;    // slot groups and slots per group
+    int rows_mode; // staging slots enumerate tile rows instead of image groups
+    int tbl_off;   // LDS byte offset of the slot table
+    int lds_bytes; // tile + slot table
+    int grid;      // workgroups launched (ntiles * kblocks rounded up to the XCD count)
     // host tables
     std::vector<Entry> entries;   // segments padded to kBatch
     std::vector<int> seg;         // [kblocks][nchunks][WK][1 + KW] = first entry, batches of each row
@@ -119,8 +125,19 @@ struct KernelArgs {
     int WP, WK, Cc, Wp, Hs, Hb, CS, span;
     int nchunks, ngroups, ntiles, kblocks;
     int tile_elems;  // Cc * CS
-    int RW;          // row slots per (group, channel) in the staging map: min(H, Hb)
-    FastDiv fd_Wp, fd_Hs, fd_W, fd_chan, fd_group;  // divisors Wp, Hs, W, RW*W, Cc*RW*W
+    // staging: a channel of the tile is SG groups of SP slots (SL = SG * SP); units are
+    // ordered (group, channel, slot-in-group) and a thread's next unit is nthreads further on
+    int SL;          // slots of one channel
+    int SG, SP;      // rows mode: 1 group of Hb*W slots; groups mode: GC image groups of H*W slots
+    int rows_mode;   // slots enumerate tile rows (Hs >= Hb) instead of image groups
+    int tbl_off;     // byte offset of the slot table in LDS (after the tile)
+    int st_dg, st_dc, st_dp; // nthreads = st_dg * (Cc * SP) + st_dc * SP + st_dp
+    int nbuf;                // tile buffers in LDS: 2 when there are several chunks
+    int npass;               // staging passes per chunk: ceil(SG * Cc * SP / (kStage * threads))
+    FastDiv fd_Wp, fd_Hs, fd_W, fd_HW, fd_SP, fd_CP;  // divisors Wp, Hs, W, H*W, SP, Cc*SP
+#ifdef SC_PHASE_TIMING
+    unsigned long long* phase;  // 8 counters per workgroup, or null
+#endif
 };
 
 // Enqueues the tile kernel.  Returns a hipError_t value (0 = success).

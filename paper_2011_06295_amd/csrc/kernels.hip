@@ -25,7 +25,6 @@
 
 namespace sc {
 
-constexpr int kStage = 4;  // tile elements a thread stages per round (loads in flight: kStage * V)
 
 // Read-only plan tables are addressed through the constant address space: a
 // wave-uniform load from it is always issued on the scalar path (s_load), which
@@ -46,6 +45,23 @@ __device__ __forceinline__ int fdiv(int n, const FastDiv& f)
     return f.d == 1 ? n : (int)(__umulhi((unsigned)n, f.mul) >> f.shift);
 }
 
+// One element through a buffer descriptor; out-of-range offsets read as zero.
+template <typename T>
+__device__ __forceinline__ T load_elem(__amdgpu_buffer_rsrc_t rs, unsigned off);
+template <>
+__device__ __forceinline__ float load_elem<float>(__amdgpu_buffer_rsrc_t rs, unsigned off)
+{
+    return __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rs, (int)off, 0, 0));
+}
+template <>
+__device__ __forceinline__ _Float16 load_elem<_Float16>(__amdgpu_buffer_rsrc_t rs, unsigned off)
+{
+    const unsigned short h = __builtin_amdgcn_raw_buffer_load_b16(rs, (int)off, 0, 0);
+    _Float16 r;
+    __builtin_memcpy(&r, &h, 2);
+    return r;
+}
+
 template <typename T, int V>
 struct Vec {
     typedef T type __attribute__((ext_vector_type(V)));
@@ -61,27 +77,50 @@ struct Vec<T, 1> {
     static __device__ __forceinline__ type zero() { return T(0); }
 };
 
+// Developer instrumentation (builds with -DSC_PHASE_TIMING only): every
+// wavefront accumulates the 100 MHz wall-clock ticks
+// spent in [0] set-up, [1] staging (incl. the wait for all stagers), [2] the
+// gather-FMA, [3] waiting for copies and the other wavefronts, [4] the
+// store, and reports [5] its start and [6] its end tick (8 counters per
+// wavefront, 16 wavefront slots per workgroup).
+#ifdef SC_PHASE_TIMING
+#define SC_PHASE(i)                                  \
+    do {                                             \
+        const unsigned long long n_ = wall_clock64(); \
+        ph_acc[i] += n_ - ph_t;                      \
+        ph_t = n_;                                   \
+    } while (0)
+#else
+#define SC_PHASE(i) \
+    do {            \
+    } while (0)
+#endif
+
 template <typename T, int V, int KW>
 __global__ __launch_bounds__(1024) void tile_kernel(const KernelArgs a)
 {
+#ifdef SC_PHASE_TIMING
+    unsigned long long ph_t = wall_clock64();
+    const unsigned long long ph_start = ph_t;
+    unsigned long long ph_acc[5] = {0, 0, 0, 0, 0};
+#endif
     using VT = Vec<T, V>;
     using vec = typename VT::type;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    vec* tile = reinterpret_cast<vec*>(smem);
 
     const int tid = threadIdx.x;
     const int nthreads = blockDim.x;
 
     // Workgroup -> (tile, channel block).  Consecutive workgroup ids go round
-    // the 8 XCDs.  Each XCD gets one contiguous range of tiles and all their
-    // channel blocks, so a tile's rows, which its neighbours and its other
-    // channel blocks stage again, are fetched into a single L2.
+    // the 8 XCDs.  The (tile, channel block) pairs, tile-major, are cut into 8
+    // equal contiguous ranges, one per XCD: the XCDs get the same number of
+    // workgroups, and a tile's rows, which its neighbours and its other channel
+    // blocks stage again, are fetched into one L2 (two where a range ends).
     const int bid = blockIdx.x;
-    const int xcd = bid & 7;
-    const int qb = bid >> 3;
-    const int kb = qb % a.kblocks;
-    const int tile_id = xcd * ((a.ntiles + 7) >> 3) + qb / a.kblocks;
-    if (tile_id >= a.ntiles || qb / a.kblocks >= ((a.ntiles + 7) >> 3)) return;
+    const int item = (bid & 7) * (int)(gridDim.x >> 3) + (bid >> 3);
+    if (item >= a.ntiles * a.kblocks) return;
+    const int tile_id = item / a.kblocks;
+    const int kb = item - tile_id * a.kblocks;
 
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lane = tid & 63;
@@ -111,66 +150,42 @@ __global__ __launch_bounds__(1024) void tile_kernel(const KernelArgs a)
 #pragma unroll
         for (int v = 0; v < V; ++v) acc[kk][v] = 0.f;
 
-    // padding rows/columns and absent images stay zero for the whole kernel
-    for (int u = tid; u < a.tile_elems; u += nthreads) tile[u] = VT::zero();
-
     const T* __restrict__ x = static_cast<const T*>(a.x);
     const int chan_stride = a.H * a.W;
     const int img_stride = a.C * chan_stride;   // the host guarantees N*C*H*W < 2^31
-
-    // Staging map.  The tile's real (non-padding) elements are enumerated group
-    // by group, inside a group channel by channel, inside a channel row by row
-    // (RW row slots per channel, RW = min(H, Hb)): in that order one image's
-    // elements are contiguous in memory across rows and channels, so consecutive
-    // lanes load consecutive addresses even when a feature map is only a few
-    // pixels large.  Slots whose row lies outside the tile are skipped.  Thread `tid` owns elements tid,
-    // tid + nthreads, ...  Decoding an element gives:
-    //   src  input element offset of image 0 of the group at chunk channel 0, or -1 for none
-    //   dc   tile element index | channel << 17 | (valid images - 1) << 28
+    const unsigned chan_bytes = (unsigned)chan_stride * (unsigned)sizeof(T);
+    const unsigned img_bytes = (unsigned)img_stride * (unsigned)sizeof(T);
+    // Input is read through a buffer descriptor that starts at the first image
+    // group of the tile (plus the chunk's first channel) and ends with the
+    // input: offsets marked invalid (>= 2^31) and images past the end of the
+    // batch are out of its range and read as zero, so no load needs a branch.
     const int g_first = fdiv(Y0, a.fd_Hs);
-    const int g_count = fdiv(Y0 + a.Hb - 1, a.fd_Hs) - g_first + 1;
-    const int chan_slots = a.RW * a.W;          // a group holds at most RW rows of the tile
-    const int group_slots = a.Cc * chan_slots;
-    const int units = g_count * group_slots;    // enumerated slots of a full chunk (some fall outside the tile)
-    auto decode = [&](int u, int& src, int& dc) {
-        const int gi = fdiv(u, a.fd_group);
-        const int rem = u - gi * group_slots;
-        const int c = fdiv(rem, a.fd_chan);
-        const int r2 = rem - c * chan_slots;
-        const int yr = fdiv(r2, a.fd_W);
-        const int xx = r2 - yr * a.W;
-        const int gs = g_first + gi;
-        int r_lo = Y0 - gs * a.Hs - a.pad;      // first input row of group gs inside the tile
-        int r_hi = r_lo + a.Hb;
-        if (r_lo < 0) r_lo = 0;
-        if (r_hi > a.H) r_hi = a.H;
-        const int ys = r_lo + yr;
-        const int Yt = gs * a.Hs + a.pad + ys - Y0;
-        const int left = a.N - gs * V;
-        const int nv = left < V ? left : V;
-        const bool ok = u < units && gs < a.ngroups && ys < r_hi;
-        src = ok ? gs * V * img_stride + c * chan_stride + ys * a.W + xx : -1;
-        dc = ok ? ((c * a.CS + Yt * a.Wp + a.pad + xx) | (c << 17) | ((nv - 1) << 28)) : 0;
+    const size_t tile_base = (size_t)g_first * V * img_bytes;
+    const size_t total_bytes = (size_t)a.N * img_bytes;
+    auto chunk_rsrc = [&](int c0) {
+        const size_t chunk_base = tile_base + (size_t)c0 * chan_bytes;
+        const size_t remain = total_bytes > chunk_base ? total_bytes - chunk_base : 0;
+        return __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(reinterpret_cast<const char*>(x)) + chunk_base, 0,
+                                                 remain > 0x80000000ull ? 0x80000000u : (unsigned)remain, 0x00020000);
     };
-    const int round_units = kStage * nthreads;
 
     // Per (channel block, chunk, wavefront) descriptor: first plan entry, then the
     // batch count of each of the KW rows; the KW segments are contiguous in the
     // entry table.  The descriptor of the next chunk and the first batch of this
-    // chunk are requested before staging starts, so their latency is hidden.
+    // chunk are requested a phase ahead, so their latency is hidden.
     const SC_CONSTANT int* sg = as_constant(a.seg) + ((size_t)kb * a.nchunks * a.WK + wk) * (KW + 1);
     const size_t sg_step = (size_t)a.WK * (KW + 1);
     int d_start = sg[0];
     int d_nb[KW];
 #pragma unroll
     for (int kk = 0; kk < KW; ++kk) d_nb[kk] = sg[1 + kk];
-
-    for (int ch = 0; ch < a.nchunks; ++ch) {
-        const SC_CONSTANT Entry* e = as_constant(a.entries) + d_start;
-        int nb[KW];
+    const SC_CONSTANT Entry* e = nullptr;
+    int nb[KW];
+    Entry cur[kBatch];
+    auto begin_chunk = [&](int ch) __attribute__((always_inline)) {
+        e = as_constant(a.entries) + d_start;
 #pragma unroll
         for (int kk = 0; kk < KW; ++kk) nb[kk] = d_nb[kk];
-        Entry cur[kBatch];
 #pragma unroll
         for (int u = 0; u < kBatch; ++u) {  // the table ends in kBatch slack entries
             cur[u].wbits = e[u].wbits;
@@ -182,59 +197,197 @@ __global__ __launch_bounds__(1024) void tile_kernel(const KernelArgs a)
 #pragma unroll
             for (int kk = 0; kk < KW; ++kk) d_nb[kk] = sg[1 + kk];
         }
+    };
 
-        __syncthreads();  // zero fill done / previous chunk fully consumed
-        // ---- stage the chunk: all loads of a round are issued before the first LDS write
-        const int c0 = ch * a.Cc;
-        const int cn = (a.C - c0) < a.Cc ? (a.C - c0) : a.Cc;
-        const T* __restrict__ xc = x + (size_t)c0 * chan_stride;
-        for (int r0 = 0; r0 < units; r0 += round_units) {
-            int src[kStage], dc[kStage];
+    // Gather-FMA over this wavefront's KW rows of one chunk whose tile starts at
+    // LDS byte `base` (already offset by the lane's position).  The stored
+    // weights of the wavefront's rows form one stream of batches; a step
+    // consumes the batch in A in two halves and requests the following batch
+    // (possibly the next row's first) into B.  While the multiply-adds of one
+    // half run, the LDS reads of the next half (and, in the first half, the
+    // scalar fetch of B) are in flight; the wait at the end of a half therefore
+    // finds them complete, and one wait serves LDS and scalar returns alike.
+    // Entry offsets are in bytes: one VOP2 add per read.
+    constexpr int kHalf = kBatch / 2;
+    static_assert(kHalf == 4, "arrived() names four registers");
+    // an empty statement that uses a half's registers: the compiler has to complete their loads before it
+    auto arrived = [](const vec(&x)[kHalf]) __attribute__((always_inline)) {
+        asm volatile("" ::"v"(x[0]), "v"(x[1]), "v"(x[2]), "v"(x[3]));
+    };
+    auto compute = [&](int base) __attribute__((always_inline)) {
+        vec xa[kHalf], xb[kHalf];
 #pragma unroll
-            for (int t = 0; t < kStage; ++t) {
-                decode(r0 + tid + t * nthreads, src[t], dc[t]);
-                if (((dc[t] >> 17) & 0x7ff) >= cn) src[t] = -1;
+        for (int u = 0; u < kHalf; ++u) xa[u] = *reinterpret_cast<const vec*>(smem + (base + cur[u].off));
+        arrived(xa);
+        auto step = [&](const Entry (&A)[kBatch], Entry (&B)[kBatch], float (&ac)[V]) __attribute__((always_inline)) {
+            // first half: multiply-adds on A[0..3] (in xa); reads of A[4..7] and the fetch of B in flight
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int u = 0; u < kHalf; ++u) xb[u] = *reinterpret_cast<const vec*>(smem + (base + A[kHalf + u].off));
+            e += kBatch;
+#pragma unroll
+            for (int u = 0; u < kBatch; ++u) {
+                B[u].wbits = e[u].wbits;
+                B[u].off = e[u].off;
             }
-            vec val[kStage];
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int t = 0; t < kStage; ++t) {
-                const int nv = ((dc[t] >> 28) & 7) + 1;
+            for (int u = 0; u < kHalf; ++u) {
+                const float w = __uint_as_float(A[u].wbits);
 #pragma unroll
-                for (int v = 0; v < V; ++v)
-                    VT::set(val[t], v, (src[t] >= 0 && v < nv) ? xc[(size_t)src[t] + (size_t)v * img_stride] : T(0));
+                for (int v = 0; v < V; ++v) ac[v] = __builtin_fmaf(w, (float)VT::get(xa[u], v), ac[v]);
             }
+            __builtin_amdgcn_sched_barrier(0);
+            arrived(xb);
+            // second half: multiply-adds on A[4..7] (in xb); reads of B[0..3] in flight
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int t = 0; t < kStage; ++t)
-                if (src[t] >= 0) tile[dc[t] & 0x1ffff] = val[t];
-        }
-        __syncthreads();
-
-        // ---- gather-FMA over this wavefront's KW rows
+            for (int u = 0; u < kHalf; ++u) xa[u] = *reinterpret_cast<const vec*>(smem + (base + B[u].off));
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int u = 0; u < kHalf; ++u) {
+                const float w = __uint_as_float(A[kHalf + u].wbits);
+#pragma unroll
+                for (int v = 0; v < V; ++v) ac[v] = __builtin_fmaf(w, (float)VT::get(xb[u], v), ac[v]);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            arrived(xa);
+        };
 #pragma unroll
         for (int kk = 0; kk < KW; ++kk) {
-            for (int b = 0; b < nb[kk]; ++b) {
-                vec xv[kBatch];
-#pragma unroll
-                for (int u = 0; u < kBatch; ++u)  // entry offsets are in bytes: one VOP2 add per read
-                    xv[u] = *reinterpret_cast<const vec*>(smem + (lposb + cur[u].off));
-                e += kBatch;
-                Entry nxt[kBatch];  // look-ahead fetch of the next batch (possibly the next row's first)
-#pragma unroll
-                for (int u = 0; u < kBatch; ++u) {
-                    nxt[u].wbits = e[u].wbits;
-                    nxt[u].off = e[u].off;
-                }
-                __builtin_amdgcn_sched_barrier(0);  // keep the LDS reads ahead of the arithmetic
-#pragma unroll
-                for (int u = 0; u < kBatch; ++u) {
-                    const float w = __uint_as_float(cur[u].wbits);
-#pragma unroll
-                    for (int v = 0; v < V; ++v)
-                        acc[kk][v] = __builtin_fmaf(w, (float)VT::get(xv[u], v), acc[kk][v]);
-                }
+            Entry nxt[kBatch];
+            int b = 0;
+            for (; b + 2 <= nb[kk]; b += 2) {
+                step(cur, nxt, acc[kk]);
+                step(nxt, cur, acc[kk]);
+            }
+            if (b < nb[kk]) {
+                step(cur, nxt, acc[kk]);
 #pragma unroll
                 for (int u = 0; u < kBatch; ++u) cur[u] = nxt[u];
             }
+        }
+    };
+
+    // ---- LDS: nbuf tile buffers (two when the channels come in several chunks), one
+    // reject element, the slot table
+    vec* tile = reinterpret_cast<vec*>(smem);
+    const int reject = a.nbuf * a.tile_elems;
+    // padding rows/columns and absent images stay zero for the whole kernel
+    for (int u = tid; u < reject; u += nthreads) tile[u] = VT::zero();
+
+    // Staging table.  What a tile holds of one channel is the same for every
+    // channel: a set of SL slots, each one real (non-padding) element of the
+    // lattice rows the tile covers.  Slots are enumerated so that neighbouring
+    // slots are neighbours in memory: row by row for maps taller than the tile,
+    // image group by image group (whole H x W planes) for small maps.  Each
+    // slot is decoded once into
+    //   .x  byte offset of image 0 of its group, relative to the first group
+    //       of the tile, at channel 0 (0x80000000: the slot is not in the tile)
+    //   .y  tile element index at channel 0
+    // and staging then only adds channel strides.
+    int2* tbl = reinterpret_cast<int2*>(smem + a.tbl_off);
+    for (int sl = tid; sl < a.SL; sl += nthreads) {
+        int gs, ys, xx, Yt;
+        if (a.rows_mode) {
+            Yt = fdiv(sl, a.fd_W);
+            xx = sl - Yt * a.W;
+            const int Ys = Y0 + Yt;
+            gs = fdiv(Ys, a.fd_Hs);
+            ys = Ys - gs * a.Hs - a.pad;
+        } else {
+            const int gi = fdiv(sl, a.fd_HW);
+            const int rem = sl - gi * chan_stride;
+            ys = fdiv(rem, a.fd_W);
+            xx = rem - ys * a.W;
+            gs = g_first + gi;
+            Yt = gs * a.Hs + a.pad + ys - Y0;
+        }
+        const bool ok = gs < a.ngroups && ys >= 0 && ys < a.H && Yt >= 0 && Yt < a.Hb;
+        int2 t;
+        // (gs - g_first) * V * img_bytes < 2^31 is guaranteed by the host
+        t.x = ok ? (int)((unsigned)((gs - g_first) * V) * img_bytes + (unsigned)(ys * a.W + xx) * (unsigned)sizeof(T))
+                 : (int)0x80000000;
+        t.y = ok ? Yt * a.Wp + a.pad + xx : 0;
+        tbl[sl] = t;
+    }
+    // first unit of this thread: (slot group, channel, slot in group)
+    const int st_g0 = fdiv(tid, a.fd_CP);
+    const int st_r0 = tid - st_g0 * a.Cc * a.SP;
+    const int st_c0 = fdiv(st_r0, a.fd_SP);
+    const int st_p0 = st_r0 - st_c0 * a.SP;
+
+    // A chunk is SG * Cc * SP units, unit u = (slot group * Cc + channel) * SP + slot: in that
+    // order consecutive units are consecutive in memory across the channels of an image.
+    // Thread `tid` owns units tid, tid + nthreads, ..., kStage of them per pass (the host
+    // sizes chunks for a single pass where it can).  Staging has two halves, so that the
+    // loads of the next chunk can be in flight while the current one is consumed: `fetch`
+    // issues the loads of the thread's next kStage units into registers, `deposit` writes
+    // them into a tile buffer.
+    vec st_val[kStage];
+    int st_dst[kStage];
+    int gi = 0, c = 0, sp = 0;  // the thread's next unit
+    auto fetch = [&](int ch, bool first) __attribute__((always_inline)) {
+        const int c0 = ch * a.Cc;
+        const int cn = (a.C - c0) < a.Cc ? (a.C - c0) : a.Cc;
+        const __amdgpu_buffer_rsrc_t rs = chunk_rsrc(c0);
+        if (first) {
+            gi = st_g0;
+            c = st_c0;
+            sp = st_p0;
+        }
+#pragma unroll
+        for (int t = 0; t < kStage; ++t) {
+            const bool in = gi < a.SG && c < cn;
+            const int ti = __umul24(gi, a.SP) + sp;
+            const int2 sd = tbl[in ? ti : 0];
+            const unsigned off = (in ? (unsigned)sd.x : 0x80000000u) + (unsigned)c * chan_bytes;
+            st_dst[t] = (in && sd.x >= 0) ? sd.y + (int)__umul24(c, a.CS) : -1;
+#pragma unroll
+            for (int v = 0; v < V; ++v) VT::set(st_val[t], v, load_elem<T>(rs, off + (unsigned)v * img_bytes));
+            // next unit of this thread
+            sp += a.st_dp;
+            const bool k1 = sp >= a.SP;
+            sp -= k1 ? a.SP : 0;
+            c += a.st_dc + (k1 ? 1 : 0);
+            const bool k2 = c >= a.Cc;
+            c -= k2 ? a.Cc : 0;
+            gi += a.st_dg + (k2 ? 1 : 0);
+        }
+    };
+    auto deposit = [&](int buf) __attribute__((always_inline)) {
+        const int base = buf * a.tile_elems;
+#pragma unroll
+        for (int t = 0; t < kStage; ++t)  // unconditional (rejects go to a spare element): no branches between the writes
+            tile[st_dst[t] >= 0 ? base + st_dst[t] : reject] = st_val[t];
+    };
+
+    begin_chunk(0);
+    __syncthreads();  // zero fill and slot table complete
+    fetch(0, true);
+    deposit(0);
+    for (int p = 1; p < a.npass; ++p) {
+        fetch(0, false);
+        deposit(0);
+    }
+    __syncthreads();  // chunk 0 is in LDS
+    SC_PHASE(0);
+    const int tile_bytes = a.tile_elems * (int)sizeof(vec);
+    for (int ch = 0; ch < a.nchunks; ++ch) {
+        const bool more = ch + 1 < a.nchunks;
+        if (more) fetch(ch + 1, true);  // in flight while this chunk is consumed
+        SC_PHASE(1);
+        compute((ch & (a.nbuf - 1)) * tile_bytes + lposb);
+        SC_PHASE(2);
+        if (more) {
+            begin_chunk(ch + 1);
+            deposit((ch + 1) & (a.nbuf - 1));
+            for (int p = 1; p < a.npass; ++p) {
+                fetch(ch + 1, false);
+                deposit((ch + 1) & (a.nbuf - 1));
+            }
+            __syncthreads();  // chunk ch+1 is in LDS; everyone is done with chunk ch's buffer
+            SC_PHASE(3);
         }
     }
 
@@ -255,6 +408,16 @@ __global__ __launch_bounds__(1024) void tile_kernel(const KernelArgs a)
             }
         }
     }
+#ifdef SC_PHASE_TIMING
+    SC_PHASE(4);
+    if (lane == 0 && a.phase) {
+        unsigned long long* o = a.phase + ((size_t)bid * 16 + wave) * 8;
+        for (int i = 0; i < 5; ++i) o[i] = ph_acc[i];
+        o[5] = ph_start;
+        o[6] = ph_t;
+        o[7] = 1;
+    }
+#endif
 }
 
 namespace {

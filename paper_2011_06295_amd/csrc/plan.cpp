@@ -29,50 +29,77 @@ constexpr int kWave = 64;
 constexpr int kMaxWaves = 16;          // wavefronts per workgroup
 constexpr int kMaxLds = 160 * 1024;    // LDS per CU
 constexpr int kCUs = 256;
-constexpr int kCUWaves = 32;           // resident wavefronts per CU at <= 64 VGPRs
 
 inline int cdiv(long long a, long long b) { return (int)((a + b - 1) / b); }
 bool pow2_in(int v, int lo, int hi) { return v >= lo && v <= hi && (v & (v - 1)) == 0; }
 
 struct Shape {
     int K, C, R, S, ub;  // ub = bytes of one LDS element (V images)
-    int V, W, Wp, Hs;
+    int V, H, W, Wp, Hs, elem_bytes;
     long long npos;
     double row_nnz;      // mean stored weights per output channel
 };
 
 struct Cand {
-    int WP, WK, KW, Cc;
-    int Hb, CS, lds;
+    int V, WP, WK, KW, Cc;
+    int Hb, CS, lds, SL, rows_mode, SG, nbuf;
 };
 
 // Tile height in lattice rows for a window of `span` positions starting anywhere in a row.
 int tile_rows(int span, int Wp, int R, int S) { return (Wp - 1 + span - 1 + (R - 1) * Wp + S - 1) / Wp + 1; }
 
-// Rough time of one launch in CU clocks.  The constants come from
-// micro-benchmarks on MI355X: a 16-byte LDS read of a wavefront occupies the
-// LDS for about 4.6 clocks once >= 16 wavefronts are resident; a wavefront's
-// VALU instruction takes ~2.4 clocks; global->LDS staging sustains ~48 B/clk/CU.
+// Rough time of one launch in CU clocks, from measurements on MI355X.
+//  * A step (kBatch stored weights of one output channel, for the 64 positions of
+//    a wavefront) costs its SIMD kBatch * (V + 1) vector instructions of ~4 clocks
+//    (fp16: the mixed-precision multiply-add takes ~4.4) and the CU's LDS
+//    kBatch * 64 elements at ~200 B/clk.  For 16-byte fp32 elements the two are
+//    equal, and when both are needed at full rate neither is reached: the inner
+//    loop was measured at ~61 % of either.
+//  * A lone wavefront cannot overlap its own LDS latency (~170 clocks a step).
+//  * Registers allow 20 resident wavefronts per CU up to KW = 2, 16 above.
+//  * Staging moves ~16 B/clk/CU from L2 and overlaps the arithmetic except for the
+//    first chunk; a workgroup costs ~3 us to start and finish.
+//  * Workgroups run in rounds of (CUs * resident workgroups); a partly filled
+//    last round still takes a round.
 double estimate(const Shape& s, const Cand& c)
 {
     const int nchunks = cdiv(s.C, c.Cc);
     const double seg = s.row_nnz * c.Cc / s.C;
-    const double padded = nchunks == 1 ? std::ceil(seg / kBatch) * kBatch : seg + 0.5 * (kBatch - 1);
+    const double batches = nchunks == 1 ? std::ceil(seg / kBatch) : seg / kBatch + 0.5;
+    const double steps_wave = c.KW * batches * nchunks * 1.1;   // 10 %: wavefronts wait for the slowest at every chunk
     const int waves = c.WP * c.WK;
+    const int maxw = c.KW <= 2 ? 20 : 16;
+    const int conc_max = std::min(kMaxLds / c.lds, maxw / waves);
+    if (conc_max < 1) return -1.0;
     const long long wgs = (long long)cdiv(s.npos, (long long)kWave * c.WP) * cdiv(s.K, c.WK * c.KW);
-    int conc = std::min(kMaxLds / c.lds, kCUWaves / waves);
-    conc = (int)std::max<long long>(1, std::min<long long>(conc, (wgs + kCUs - 1) / kCUs));
-    const double reads_wave = c.KW * padded * nchunks;
-    const double resident = (double)conc * waves;
-    const double lds_clk = resident < 16 ? 4.6 * 16.0 / resident : 4.6;   // latency-bound below 16 wavefronts
-    const double t_lds = conc * waves * reads_wave * lds_clk;
-    const double t_valu = (resident / 4.0) * reads_wave * (s.V + 1) * 2.4;
-    const double fill_bytes = (double)s.C * c.Hb * s.W * s.ub;
-    const double t_fill = conc * fill_bytes / 48.0;
-    const double t_fixed = 3000.0 + nchunks * (700.0 + 60.0 * c.KW);
-    const double per_round = std::max(t_lds, t_valu) + t_fill + t_fixed;
-    const double rounds = std::ceil((double)wgs / ((double)kCUs * conc));
-    return rounds * per_round;
+    const double fma_clk = s.elem_bytes == 2 ? 4.4 : 4.0;
+    const double v_step = kBatch * (c.V * fma_clk + 4.0);
+    const double l_step = kBatch * 64.0 * s.ub / 200.0;
+    const double gbytes = (double)s.C * c.CS * s.ub * ((double)s.W / s.Wp) * std::min(1.0, (double)s.H / s.Hs);
+    const double fixed = 7000.0 + 400.0 * nchunks;
+    double t = 0.0;
+    long long remaining = wgs;
+    const long long slots = (long long)kCUs * conc_max;
+    while (remaining > 0) {
+        const long long n = std::min(remaining, slots);
+        const int conc = (int)((n + kCUs - 1) / kCUs);
+        const double W = (double)conc * waves;
+        const double a = W * v_step / 4.0, b = W * l_step;
+        const double shared = (std::max(a, b) + 0.5 * std::min(a, b)) / 0.92;
+        const double step_clk = std::max(shared, v_step + 170.0);
+        const double t_compute = steps_wave * step_clk;
+        const double t_stage = conc * gbytes / 16.0;
+        const long long full = remaining / slots;
+        const double round = std::max(t_compute, t_stage) + t_stage / nchunks + fixed;
+        if (full > 1) {            // identical full rounds
+            t += round * (double)full;
+            remaining -= full * slots;
+        } else {
+            t += round;
+            remaining -= n;
+        }
+    }
+    return t;
 }
 
 }  // namespace
@@ -98,72 +125,104 @@ int build_plan(const Csr& csr, int C, int R, int S, int elem_bytes, const Geomet
     p.E = (g.H + 2 * pad - R) / st + 1;
     p.F = (g.W + 2 * pad - S) / st + 1;
 
-    // ---- images interleaved per LDS element: as wide an element as the batch can fill (16 bytes at most)
-    int V = over.V;
-    const int vmax = 16 / elem_bytes;
-    if (V == 0) {
-        V = vmax;
-        while (V > 1 && V / 2 >= g.N) V /= 2;
-    }
-    if (!pow2_in(V, 1, vmax)) return SC_EINVAL;
-
-    Shape s;
-    s.K = K; s.C = C; s.R = R; s.S = S;
-    s.V = V;
-    s.ub = V * elem_bytes;
-    s.W = g.W;
-    // pitch and group height: the padding below/right of an image is shared with the
-    // next group/row, but every output's receptive field must still start inside its own group
-    s.Wp = std::max(g.W + pad, (p.F - 1) * st + 1);
-    s.Hs = std::max(g.H + pad, (p.E - 1) * st + 1);
-    const int ngroups = std::max(1, cdiv(g.N, V));
-    s.npos = (long long)ngroups * s.Hs * s.Wp;
-    s.row_nnz = K > 0 ? (double)csr.colidx.size() / K : 0.0;
-    if (s.npos + 1024 >= (1ll << 31)) return SC_EUNSUPPORTED;  // positions are 32-bit in the kernel
-
     if (over.lds_budget > kMaxLds) return SC_EINVAL;
     if (over.KW && !pow2_in(over.KW, 1, 16)) return SC_EINVAL;
     if (over.WP * std::max(1, over.WK) > kMaxWaves || over.WK > kMaxWaves) return SC_EINVAL;
+    const int vmax = 16 / elem_bytes;
+    if (over.V && !pow2_in(over.V, 1, vmax)) return SC_EINVAL;
 
     // ---- candidates
-    static const int budgets[] = {40 * 1024, 52 * 1024, 80 * 1024, 160 * 1024};
+    static const int budgets[] = {160 * 1024, 80 * 1024, 53 * 1024, 40 * 1024, 32 * 1024};
     Cand best{};
+    Shape bs{};
     double best_t = -1.0;
-    for (int WP = 1; WP <= 8; WP *= 2) {
-        if (over.WP && WP != 1) break;
-        const int wp = over.WP ? over.WP : WP;
-        const int Hb = tile_rows(kWave * wp, s.Wp, R, S);
-        const long long CS = (long long)Hb * s.Wp;
-        for (int WK = 1; WK <= kMaxWaves; WK *= 2) {
-            if (over.WK && WK != 1) break;
-            const int wk = over.WK ? over.WK : WK;
-            if (wp * wk > kMaxWaves) continue;
-            for (int KW = 1; KW <= 16; KW *= 2) {
-                if (over.KW && KW != 1) break;
-                const int kw = over.KW ? over.KW : KW;
-                if (kw * V > 64) continue;                       // accumulators must stay in registers
-                if (!over.KW && !over.WK && (long long)wk * kw >= 2ll * K && wk * kw > 1) continue;
-                for (int bi = 0; bi < 4; ++bi) {
-                    if ((over.lds_budget || over.Cc) && bi) break;
-                    const int budget = over.lds_budget ? over.lds_budget : budgets[bi];
-                    int Cc = over.Cc ? std::min(over.Cc, C) : (int)std::min<long long>(C, budget / (CS * s.ub));
-                    if (Cc < 1) continue;
-                    Cc = std::min(Cc, 2047);                     // the staging map keeps the channel in 11 bits
-                    if (!over.Cc) Cc = cdiv(C, cdiv(C, Cc));     // even chunks
-                    const long long lds = (long long)Cc * CS * s.ub;
-                    if (lds > kMaxLds) continue;
-                    Cand c{wp, wk, kw, Cc, Hb, (int)CS, (int)lds};
-                    const double t = estimate(s, c);
-                    if (best_t < 0 || t < best_t) {
-                        best_t = t;
-                        best = c;
+    bool too_many_positions = false;
+    // images interleaved per LDS element: an element of up to 16 bytes, not wider than the batch can fill
+    for (int V = vmax; V >= 1; V /= 2) {
+        if (over.V && V != over.V) continue;
+        if (!over.V && V > 1 && V / 2 >= g.N) continue;
+        Shape s;
+        s.K = K; s.C = C; s.R = R; s.S = S;
+        s.V = V;
+        s.elem_bytes = elem_bytes;
+        s.ub = V * elem_bytes;
+        s.H = g.H; s.W = g.W;
+        // pitch and group height: the padding below/right of an image is shared with the
+        // next group/row, but every output's receptive field must still start inside its own group
+        s.Wp = std::max(g.W + pad, (p.F - 1) * st + 1);
+        s.Hs = std::max(g.H + pad, (p.E - 1) * st + 1);
+        const int ngroups = std::max(1, cdiv(g.N, V));
+        s.npos = (long long)ngroups * s.Hs * s.Wp;
+        s.row_nnz = K > 0 ? (double)csr.colidx.size() / K : 0.0;
+        if (s.npos + 1024 >= (1ll << 31)) {  // positions are 32-bit in the kernel
+            too_many_positions = true;
+            continue;
+        }
+        for (int WP = 1; WP <= 8; WP *= 2) {
+            if (over.WP && WP != 1) break;
+            const int wp = over.WP ? over.WP : WP;
+            const int Hb = tile_rows(kWave * wp, s.Wp, R, S);
+            const long long CS = (long long)Hb * s.Wp;
+            // staging slots per channel: the tile's rows, or (small maps) the whole planes of every group it can touch
+            const bool rows_mode = s.Hs >= Hb;
+            const long long GC = rows_mode ? 2 : (Hb + s.Hs - 2) / s.Hs + 1;
+            const long long SL = rows_mode ? (long long)Hb * g.W : GC * g.H * g.W;
+            const long long tbl = SL * 8;
+            // slot offsets are 31-bit byte offsets from the first image group of a tile
+            if (GC * V * C * g.H * g.W * elem_bytes >= (1ll << 31)) continue;
+            for (int WK = 1; WK <= kMaxWaves; ++WK) {
+                if (over.WK && WK != 1) break;
+                const int wk = over.WK ? over.WK : WK;
+                if (wp * wk > kMaxWaves) continue;
+                for (int KW = 1; KW <= 16; KW *= 2) {
+                    if (over.KW && KW != 1) break;
+                    const int kw = over.KW ? over.KW : KW;
+                    if (kw * V > 64) continue;                       // accumulators must stay in registers
+                    if (!over.KW && !over.WK && (long long)(wk - 1) * kw >= K && wk > 1) continue;  // idle wavefronts
+                    for (int bi = 0; bi < 5; ++bi) {
+                        if ((over.lds_budget || over.Cc) && bi) break;
+                        const int budget = over.lds_budget ? over.lds_budget : budgets[bi];
+                        const long long room = budget - tbl - 32;
+                        // a chunk should not exceed what the workgroup stages in one pass (kStage units a thread)
+                        const long long pass_cc = std::max<long long>(1, (long long)kStage * kWave * wp * wk / SL);
+                        int Cc, nbuf = 1;
+                        if (over.Cc) {
+                            Cc = std::min(over.Cc, C);
+                        } else if (room < CS * s.ub) {
+                            continue;
+                        } else if (C <= pass_cc && C * CS * s.ub <= room) {
+                            Cc = C;                                   // everything in one chunk
+                        } else {
+                            Cc = (int)std::min<long long>(std::min<long long>(C, pass_cc), room / (2 * CS * s.ub));
+                        }
+                        if (Cc < 1) continue;
+                        if (!over.Cc) Cc = cdiv(C, cdiv(C, Cc));     // even chunks
+                        if (Cc < C) nbuf = 2;                        // the next chunk lands while this one is consumed
+                        // tile buffer(s), one reject element, table
+                        const long long lds = (((long long)nbuf * Cc * CS + 1) * s.ub + 15) / 16 * 16 + tbl;
+                        if (lds > kMaxLds) continue;
+                        Cand c{V, wp, wk, kw, Cc, Hb, (int)CS, (int)lds, (int)SL, rows_mode ? 1 : 0, rows_mode ? 1 : (int)GC, nbuf};
+                        double t = estimate(s, c);
+                        if (t < 0) {
+                            if (!(over.WP || over.WK || over.KW || over.Cc || over.lds_budget)) continue;
+                            t = 1e30;   // an explicit request is honoured even where the estimate expects no residency
+                        }
+                        if (best_t < 0 || t < best_t) {
+                            best_t = t;
+                            best = c;
+                            bs = s;
+                        }
                     }
                 }
             }
         }
     }
+    if (best_t < 0 && too_many_positions) return SC_EUNSUPPORTED;
     if (best_t < 0) return SC_EUNSUPPORTED;
 
+    const Shape& s = bs;
+    const int V = best.V;
+    const int ngroups = std::max(1, cdiv(g.N, V));
     p.V = V; p.WP = best.WP; p.WK = best.WK; p.KW = best.KW; p.Cc = best.Cc;
     p.Wp = s.Wp; p.Hs = s.Hs;
     p.span = kWave * p.WP;
@@ -176,8 +235,14 @@ int build_plan(const Csr& csr, int C, int R, int S, int elem_bytes, const Geomet
     p.kblocks = cdiv(K, KB);
     p.threads = kWave * p.WP * p.WK;
     p.lds_bytes = best.lds;
-    const long long grid = (ntiles + 7) / 8 * 8 * p.kblocks;
-    if (ntiles > INT_MAX / 2 || grid > INT_MAX) return SC_EUNSUPPORTED;
+    p.SL = best.SL;
+    p.SG = best.SG;
+    p.SP = best.SL / best.SG;
+    p.rows_mode = best.rows_mode;
+    p.nbuf = best.nbuf;
+    p.tbl_off = ((p.nbuf * p.Cc * p.CS + 1) * s.ub + 15) / 16 * 16;
+    const long long grid = (ntiles * p.kblocks + 7) / 8 * 8;   // a multiple of the XCD count
+    if (ntiles > INT_MAX / 2 || grid > INT_MAX - 8) return SC_EUNSUPPORTED;
     p.ntiles = (int)ntiles;
     p.grid = (int)grid;
 
