@@ -126,19 +126,19 @@ def main():
     gpu_ms = ev0.elapsed_time(ev1)
     ms_per_step = wall * 1e3 / args.steps
 
-    # per-layer durations: events around each launch on the launch stream
+    # per-layer durations, in the order and cache state of a step: events between the launches of
+    # further (untimed) steps on the launch stream
     reps = max(10, min(args.steps, 50))
+    marks = [[torch.cuda.Event(enable_timing=True) for _ in range(len(net.runs) + 1)] for _ in range(reps)]
+    for ev in marks:
+        ev[0].record()
+        for i, r in enumerate(net.runs):
+            r.layer.forward(r.x, r.spec.stride, r.spec.pad, out=r.y)
+            ev[i + 1].record()
+    torch.cuda.synchronize()
     layers = []
-    for r in net.runs:
-        for _ in range(3):
-            r.layer.forward(r.x, r.spec.stride, r.spec.pad, out=r.y)
-        a, z = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        a.record()
-        for _ in range(reps):
-            r.layer.forward(r.x, r.spec.stride, r.spec.pad, out=r.y)
-        z.record()
-        torch.cuda.synchronize()
-        t = a.elapsed_time(z) * 1e-3 / reps
+    for i, r in enumerate(net.runs):
+        t = sum(ev[i].elapsed_time(ev[i + 1]) for ev in marks) * 1e-3 / reps
         roofs = layer_roofs(r, N, b)
         bound = max(("hbm", roofs["t_hbm"]), ("lds", roofs["t_lds"]), ("alu", roofs["t_valu"]), key=lambda kv: kv[1])
         layers.append({

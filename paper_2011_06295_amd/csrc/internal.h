@@ -92,7 +92,8 @@ struct Plan {
     int grid;      // workgroups launched (ntiles * kblocks rounded up to the XCD count)
     // host tables
     std::vector<Entry> entries;   // segments padded to kBatch
-    std::vector<int> seg;         // [kblocks][nchunks][WK][1 + KW] = first entry, batches of each row
+    std::vector<int> seg;         // [kblocks][nchunks][WK][1 + KW] = first entry, batches of each row; then one
+                                  // terminal descriptor whose first entry is the end of the last segment
     std::vector<int> krow;        // [kblocks][WK][KW] output channel or -1
     // device copies (owned)
     void* d_entries = nullptr;

@@ -176,6 +176,7 @@ __global__ __launch_bounds__(1024) void tile_kernel(const KernelArgs a)
     const SC_CONSTANT int* sg = as_constant(a.seg) + ((size_t)kb * a.nchunks * a.WK + wk) * (KW + 1);
     const size_t sg_step = (size_t)a.WK * (KW + 1);
     int d_start = sg[0];
+    int d_end = sg[KW + 1];  // the next descriptor's first entry: segments are laid out in descriptor order
     int d_nb[KW];
 #pragma unroll
     for (int kk = 0; kk < KW; ++kk) d_nb[kk] = sg[1 + kk];
@@ -194,10 +195,20 @@ __global__ __launch_bounds__(1024) void tile_kernel(const KernelArgs a)
         if (ch + 1 < a.nchunks) {
             sg += sg_step;
             d_start = sg[0];
+            d_end = sg[KW + 1];
 #pragma unroll
             for (int kk = 0; kk < KW; ++kk) d_nb[kk] = sg[1 + kk];
         }
     };
+    // The entries of a wavefront's segment are read once, batch by batch, through the scalar
+    // cache; coming from HBM each batch would cost a full memory latency.  One vector load per
+    // 64 bytes of the coming segment (d_start..d_end), issued a chunk ahead, brings the lines
+    // into L2 first.  The loaded value is only kept until the next wait for staged data.
+    auto touch = [&]() __attribute__((always_inline)) -> unsigned {
+        const int first = d_start + lane * 8;  // 8 entries = 64 bytes
+        return first < d_end ? reinterpret_cast<const unsigned*>(a.entries + first)[0] : 0u;
+    };
+    auto retire = [](unsigned t) __attribute__((always_inline)) { asm volatile("" ::"v"(t)); };
 
     // Gather-FMA over this wavefront's KW rows of one chunk whose tile starts at
     // LDS byte `base` (already offset by the lane's position).  The stored
@@ -362,6 +373,7 @@ __global__ __launch_bounds__(1024) void tile_kernel(const KernelArgs a)
             tile[st_dst[t] >= 0 ? base + st_dst[t] : reject] = st_val[t];
     };
 
+    unsigned warm = touch();  // chunk 0's entries
     begin_chunk(0);
     __syncthreads();  // zero fill and slot table complete
     fetch(0, true);
@@ -370,18 +382,23 @@ __global__ __launch_bounds__(1024) void tile_kernel(const KernelArgs a)
         fetch(0, false);
         deposit(0);
     }
+    retire(warm);
     __syncthreads();  // chunk 0 is in LDS
     SC_PHASE(0);
     const int tile_bytes = a.tile_elems * (int)sizeof(vec);
     for (int ch = 0; ch < a.nchunks; ++ch) {
         const bool more = ch + 1 < a.nchunks;
-        if (more) fetch(ch + 1, true);  // in flight while this chunk is consumed
+        if (more) {
+            warm = touch();           // chunk ch+1's entries (its descriptor was requested a chunk ago)
+            fetch(ch + 1, true);      // in flight while this chunk is consumed
+        }
         SC_PHASE(1);
         compute((ch & (a.nbuf - 1)) * tile_bytes + lposb);
         SC_PHASE(2);
         if (more) {
             begin_chunk(ch + 1);
             deposit((ch + 1) & (a.nbuf - 1));
+            retire(warm);
             for (int p = 1; p < a.npass; ++p) {
                 fetch(ch + 1, false);
                 deposit((ch + 1) & (a.nbuf - 1));

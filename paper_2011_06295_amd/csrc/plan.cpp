@@ -164,8 +164,9 @@ int build_plan(const Csr& csr, int C, int R, int S, int elem_bytes, const Geomet
             const int Hb = tile_rows(kWave * wp, s.Wp, R, S);
             const long long CS = (long long)Hb * s.Wp;
             // staging slots per channel: the tile's rows, or (small maps) the whole planes of every group it can touch
-            const bool rows_mode = s.Hs >= Hb;
-            const long long GC = rows_mode ? 2 : (Hb + s.Hs - 2) / s.Hs + 1;
+            // (whole planes only where a plane is a short run of memory: the order then continues across channels)
+            const long long GC = (Hb + s.Hs - 2) / s.Hs + 1;      // image groups a tile can touch
+            const bool rows_mode = s.Hs >= Hb || (long long)g.H * g.W * elem_bytes >= 128;
             const long long SL = rows_mode ? (long long)Hb * g.W : GC * g.H * g.W;
             const long long tbl = SL * 8;
             // slot offsets are 31-bit byte offsets from the first image group of a tile
@@ -253,7 +254,7 @@ int build_plan(const Csr& csr, int C, int R, int S, int elem_bytes, const Geomet
     const int RS = R * S;
     const int nchunks = p.nchunks;
     const int SW = p.KW + 1;  // descriptor: first entry, then batches of each of the KW rows
-    p.seg.assign((size_t)p.kblocks * nchunks * p.WK * SW, 0);
+    p.seg.assign(((size_t)p.kblocks * nchunks * p.WK + 1) * SW, 0);   // one terminal descriptor
     p.entries.clear();
     for (int kb = 0; kb < p.kblocks; ++kb)
         for (int ch = 0; ch < nchunks; ++ch) {
@@ -289,6 +290,7 @@ int build_plan(const Csr& csr, int C, int R, int S, int elem_bytes, const Geomet
                 }
             }
         }
+    p.seg[(size_t)p.kblocks * nchunks * p.WK * SW] = (int)p.entries.size();  // where the last segment ends
     for (int t = 0; t < kBatch; ++t) p.entries.push_back(Entry{0u, 0});  // slack for look-ahead fetches
     return SC_OK;
 }
