@@ -210,76 +210,6 @@ __global__ __launch_bounds__(1024) void tile_kernel(const KernelArgs a)
     };
     auto retire = [](unsigned t) __attribute__((always_inline)) { asm volatile("" ::"v"(t)); };
 
-    // Gather-FMA over this wavefront's KW rows of one chunk whose tile starts at
-    // LDS byte `base` (already offset by the lane's position).  The stored
-    // weights of the wavefront's rows form one stream of batches; a step
-    // consumes the batch in A in two halves and requests the following batch
-    // (possibly the next row's first) into B.  While the multiply-adds of one
-    // half run, the LDS reads of the next half (and, in the first half, the
-    // scalar fetch of B) are in flight; the wait at the end of a half therefore
-    // finds them complete, and one wait serves LDS and scalar returns alike.
-    // Entry offsets are in bytes: one VOP2 add per read.
-    constexpr int kHalf = kBatch / 2;
-    static_assert(kHalf == 4, "arrived() names four registers");
-    // an empty statement that uses a half's registers: the compiler has to complete their loads before it
-    auto arrived = [](const vec(&x)[kHalf]) __attribute__((always_inline)) {
-        asm volatile("" ::"v"(x[0]), "v"(x[1]), "v"(x[2]), "v"(x[3]));
-    };
-    auto compute = [&](int base) __attribute__((always_inline)) {
-        vec xa[kHalf], xb[kHalf];
-#pragma unroll
-        for (int u = 0; u < kHalf; ++u) xa[u] = *reinterpret_cast<const vec*>(smem + (base + cur[u].off));
-        arrived(xa);
-        auto step = [&](const Entry (&A)[kBatch], Entry (&B)[kBatch], float (&ac)[V]) __attribute__((always_inline)) {
-            // first half: multiply-adds on A[0..3] (in xa); reads of A[4..7] and the fetch of B in flight
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int u = 0; u < kHalf; ++u) xb[u] = *reinterpret_cast<const vec*>(smem + (base + A[kHalf + u].off));
-            e += kBatch;
-#pragma unroll
-            for (int u = 0; u < kBatch; ++u) {
-                B[u].wbits = e[u].wbits;
-                B[u].off = e[u].off;
-            }
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int u = 0; u < kHalf; ++u) {
-                const float w = __uint_as_float(A[u].wbits);
-#pragma unroll
-                for (int v = 0; v < V; ++v) ac[v] = __builtin_fmaf(w, (float)VT::get(xa[u], v), ac[v]);
-            }
-            __builtin_amdgcn_sched_barrier(0);
-            arrived(xb);
-            // second half: multiply-adds on A[4..7] (in xb); reads of B[0..3] in flight
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int u = 0; u < kHalf; ++u) xa[u] = *reinterpret_cast<const vec*>(smem + (base + B[u].off));
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int u = 0; u < kHalf; ++u) {
-                const float w = __uint_as_float(A[kHalf + u].wbits);
-#pragma unroll
-                for (int v = 0; v < V; ++v) ac[v] = __builtin_fmaf(w, (float)VT::get(xb[u], v), ac[v]);
-            }
-            __builtin_amdgcn_sched_barrier(0);
-            arrived(xa);
-        };
-#pragma unroll
-        for (int kk = 0; kk < KW; ++kk) {
-            Entry nxt[kBatch];
-            int b = 0;
-            for (; b + 2 <= nb[kk]; b += 2) {
-                step(cur, nxt, acc[kk]);
-                step(nxt, cur, acc[kk]);
-            }
-            if (b < nb[kk]) {
-                step(cur, nxt, acc[kk]);
-#pragma unroll
-                for (int u = 0; u < kBatch; ++u) cur[u] = nxt[u];
-            }
-        }
-    };
-
     // ---- LDS: nbuf tile buffers (two when the channels come in several chunks), one
     // reject element, the slot table
     vec* tile = reinterpret_cast<vec*>(smem);
@@ -322,64 +252,173 @@ __global__ __launch_bounds__(1024) void tile_kernel(const KernelArgs a)
         t.y = ok ? Yt * a.Wp + a.pad + xx : 0;
         tbl[sl] = t;
     }
-    // first unit of this thread: (slot group, channel, slot in group)
-    const int st_g0 = fdiv(tid, a.fd_CP);
-    const int st_r0 = tid - st_g0 * a.Cc * a.SP;
-    const int st_c0 = fdiv(st_r0, a.fd_SP);
-    const int st_p0 = st_r0 - st_c0 * a.SP;
-
     // A chunk is SG * Cc * SP units, unit u = (slot group * Cc + channel) * SP + slot: in that
     // order consecutive units are consecutive in memory across the channels of an image.
     // Thread `tid` owns units tid, tid + nthreads, ..., kStage of them per pass (the host
     // sizes chunks for a single pass where it can).  Staging has two halves, so that the
-    // loads of the next chunk can be in flight while the current one is consumed: `fetch`
-    // issues the loads of the thread's next kStage units into registers, `deposit` writes
-    // them into a tile buffer.
+    // loads of the next chunk can be in flight while the current one is consumed:
+    // `fetch_unit` issues the loads of one unit into registers (the units of the next chunk
+    // are spread over the rows of the current one, so that the wavefronts of a workgroup do
+    // not all queue on the memory pipeline at once), `deposit` writes them into a tile buffer.
+    // A thread's units of the first pass are the same in every chunk (only the descriptor's
+    // base moves on), so their source offset and tile element are worked out once, after
+    // the table is complete (`prepare_units`).  In a short last chunk the units of absent
+    // channels load whatever follows in memory (or zero past the end) into tile channels
+    // that no plan entry refers to.
     vec st_val[kStage];
-    int st_dst[kStage];
-    int gi = 0, c = 0, sp = 0;  // the thread's next unit
-    auto fetch = [&](int ch, bool first) __attribute__((always_inline)) {
+    int st_dst[kStage];            // tile element of the unit in flight
+    unsigned u_off[kStage];        // first pass: source offset (0x80000000: none) ...
+    int u_dst[kStage];             // ... and tile element (the reject element if none)
+    int gi = 0, c = 0, sp = 0;     // later passes: the thread's next unit
+    int f_cn = 0;                  // later passes: channels of the chunk being fetched
+    __amdgpu_buffer_rsrc_t f_rs = chunk_rsrc(0);
+    auto next_unit = [&]() __attribute__((always_inline)) {
+        sp += a.st_dp;
+        const bool k1 = sp >= a.SP;
+        sp -= k1 ? a.SP : 0;
+        c += a.st_dc + (k1 ? 1 : 0);
+        const bool k2 = c >= a.Cc;
+        c -= k2 ? a.Cc : 0;
+        gi += a.st_dg + (k2 ? 1 : 0);
+    };
+    auto prepare_units = [&]() __attribute__((always_inline)) {
+        gi = fdiv(tid, a.fd_CP);
+        const int r0 = tid - gi * a.Cc * a.SP;
+        c = fdiv(r0, a.fd_SP);
+        sp = r0 - c * a.SP;
+#pragma unroll
+        for (int t = 0; t < kStage; ++t) {
+            const bool in = gi < a.SG;
+            const int2 sd = tbl[in ? (int)__umul24(gi, a.SP) + sp : 0];
+            const bool ok = in && sd.x >= 0;
+            u_off[t] = ok ? (unsigned)sd.x + (unsigned)c * chan_bytes : 0x80000000u;
+            u_dst[t] = ok ? sd.y + (int)__umul24(c, a.CS) : reject;
+            next_unit();
+        }
+    };
+    auto fetch_begin = [&](int ch) __attribute__((always_inline)) {
         const int c0 = ch * a.Cc;
-        const int cn = (a.C - c0) < a.Cc ? (a.C - c0) : a.Cc;
-        const __amdgpu_buffer_rsrc_t rs = chunk_rsrc(c0);
-        if (first) {
-            gi = st_g0;
-            c = st_c0;
-            sp = st_p0;
+        f_cn = (a.C - c0) < a.Cc ? (a.C - c0) : a.Cc;
+        f_rs = chunk_rsrc(c0);
+    };
+    auto fetch_unit = [&](int t) __attribute__((always_inline)) {  // first pass; t is a constant after unrolling
+        st_dst[t] = u_dst[t];
+        unsigned ib = img_bytes;
+        asm volatile("" : "+s"(ib));  // keeps the V offsets from being precomputed for all units (registers)
+#pragma unroll
+        for (int v = 0; v < V; ++v) VT::set(st_val[t], v, load_elem<T>(f_rs, u_off[t] + (unsigned)v * ib));
+    };
+    auto fetch_more = [&](int p) __attribute__((always_inline)) {  // pass p >= 1: units decoded on the fly
+        if (p == 1) {  // (gi, c, sp) of unit tid + kStage * nthreads
+            gi = fdiv(tid, a.fd_CP);
+            const int r0 = tid - gi * a.Cc * a.SP;
+            c = fdiv(r0, a.fd_SP);
+            sp = r0 - c * a.SP;
+            for (int t = 0; t < kStage; ++t) next_unit();
         }
 #pragma unroll
         for (int t = 0; t < kStage; ++t) {
-            const bool in = gi < a.SG && c < cn;
-            const int ti = __umul24(gi, a.SP) + sp;
-            const int2 sd = tbl[in ? ti : 0];
-            const unsigned off = (in ? (unsigned)sd.x : 0x80000000u) + (unsigned)c * chan_bytes;
-            st_dst[t] = (in && sd.x >= 0) ? sd.y + (int)__umul24(c, a.CS) : -1;
+            const bool in = gi < a.SG && c < f_cn;
+            const int2 sd = tbl[in ? (int)__umul24(gi, a.SP) + sp : 0];
+            const bool ok = in && sd.x >= 0;
+            const unsigned off = ok ? (unsigned)sd.x + (unsigned)c * chan_bytes : 0x80000000u;
+            st_dst[t] = ok ? sd.y + (int)__umul24(c, a.CS) : reject;
 #pragma unroll
-            for (int v = 0; v < V; ++v) VT::set(st_val[t], v, load_elem<T>(rs, off + (unsigned)v * img_bytes));
-            // next unit of this thread
-            sp += a.st_dp;
-            const bool k1 = sp >= a.SP;
-            sp -= k1 ? a.SP : 0;
-            c += a.st_dc + (k1 ? 1 : 0);
-            const bool k2 = c >= a.Cc;
-            c -= k2 ? a.Cc : 0;
-            gi += a.st_dg + (k2 ? 1 : 0);
+            for (int v = 0; v < V; ++v) VT::set(st_val[t], v, load_elem<T>(f_rs, off + (unsigned)v * img_bytes));
+            next_unit();
         }
     };
     auto deposit = [&](int buf) __attribute__((always_inline)) {
         const int base = buf * a.tile_elems;
 #pragma unroll
         for (int t = 0; t < kStage; ++t)  // unconditional (rejects go to a spare element): no branches between the writes
-            tile[st_dst[t] >= 0 ? base + st_dst[t] : reject] = st_val[t];
+            tile[st_dst[t] == reject ? reject : base + st_dst[t]] = st_val[t];
+    };
+
+    // Gather-FMA over this wavefront's KW rows of one chunk whose tile starts at
+    // LDS byte `base` (already offset by the lane's position).  The stored
+    // weights of the wavefront's rows form one stream of batches; a step
+    // consumes the batch in A in two halves and requests the following batch
+    // (possibly the next row's first) into B.  While the multiply-adds of one
+    // half run, the LDS reads of the next half (and, in the first half, the
+    // scalar fetch of B) are in flight; the wait at the end of a half therefore
+    // finds them complete, and one wait serves LDS and scalar returns alike.
+    // Entry offsets are in bytes: one VOP2 add per read.
+    constexpr int kHalf = kBatch / 2;
+    static_assert(kHalf == 4, "arrived() names four registers");
+    // an empty statement that uses a half's registers: the compiler has to complete their loads before it
+    auto arrived = [](const vec(&x)[kHalf]) __attribute__((always_inline)) {
+        asm volatile("" ::"v"(x[0]), "v"(x[1]), "v"(x[2]), "v"(x[3]));
+    };
+    auto compute = [&](int base, bool prefetch) __attribute__((always_inline)) {
+        vec xa[kHalf], xb[kHalf];
+#pragma unroll
+        for (int u = 0; u < kHalf; ++u) xa[u] = *reinterpret_cast<const vec*>(smem + (base + cur[u].off));
+        arrived(xa);
+        auto step = [&](const Entry (&A)[kBatch], Entry (&B)[kBatch], float (&ac)[V]) __attribute__((always_inline)) {
+            // first half: multiply-adds on A[0..3] (in xa); reads of A[4..7] and the fetch of B in flight
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int u = 0; u < kHalf; ++u) xb[u] = *reinterpret_cast<const vec*>(smem + (base + A[kHalf + u].off));
+            e += kBatch;
+#pragma unroll
+            for (int u = 0; u < kBatch; ++u) {
+                B[u].wbits = e[u].wbits;
+                B[u].off = e[u].off;
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int u = 0; u < kHalf; ++u) {
+                const float w = __uint_as_float(A[u].wbits);
+#pragma unroll
+                for (int v = 0; v < V; ++v) ac[v] = __builtin_fmaf(w, (float)VT::get(xa[u], v), ac[v]);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            arrived(xb);
+            // second half: multiply-adds on A[4..7] (in xb); reads of B[0..3] in flight
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int u = 0; u < kHalf; ++u) xa[u] = *reinterpret_cast<const vec*>(smem + (base + B[u].off));
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int u = 0; u < kHalf; ++u) {
+                const float w = __uint_as_float(A[kHalf + u].wbits);
+#pragma unroll
+                for (int v = 0; v < V; ++v) ac[v] = __builtin_fmaf(w, (float)VT::get(xb[u], v), ac[v]);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            arrived(xa);
+        };
+#pragma unroll
+        for (int kk = 0; kk < KW; ++kk) {
+            if (prefetch) {  // this row's share of the next chunk's staging loads
+#pragma unroll
+                for (int t = kk * kStage / KW; t < (kk + 1) * kStage / KW; ++t) fetch_unit(t);
+            }
+            Entry nxt[kBatch];
+            int b = 0;
+            for (; b + 2 <= nb[kk]; b += 2) {
+                step(cur, nxt, acc[kk]);
+                step(nxt, cur, acc[kk]);
+            }
+            if (b < nb[kk]) {
+                step(cur, nxt, acc[kk]);
+#pragma unroll
+                for (int u = 0; u < kBatch; ++u) cur[u] = nxt[u];
+            }
+        }
     };
 
     unsigned warm = touch();  // chunk 0's entries
     begin_chunk(0);
     __syncthreads();  // zero fill and slot table complete
-    fetch(0, true);
+    prepare_units();
+    fetch_begin(0);
+#pragma unroll
+    for (int t = 0; t < kStage; ++t) fetch_unit(t);
     deposit(0);
     for (int p = 1; p < a.npass; ++p) {
-        fetch(0, false);
+        fetch_more(p);
         deposit(0);
     }
     retire(warm);
@@ -390,17 +429,17 @@ __global__ __launch_bounds__(1024) void tile_kernel(const KernelArgs a)
         const bool more = ch + 1 < a.nchunks;
         if (more) {
             warm = touch();           // chunk ch+1's entries (its descriptor was requested a chunk ago)
-            fetch(ch + 1, true);      // in flight while this chunk is consumed
+            fetch_begin(ch + 1);
         }
         SC_PHASE(1);
-        compute((ch & (a.nbuf - 1)) * tile_bytes + lposb);
+        compute((ch & (a.nbuf - 1)) * tile_bytes + lposb, more);  // chunk ch+1's loads are issued along the way
         SC_PHASE(2);
         if (more) {
             begin_chunk(ch + 1);
             deposit((ch + 1) & (a.nbuf - 1));
             retire(warm);
             for (int p = 1; p < a.npass; ++p) {
-                fetch(ch + 1, false);
+                fetch_more(p);
                 deposit((ch + 1) & (a.nbuf - 1));
             }
             __syncthreads();  // chunk ch+1 is in LDS; everyone is done with chunk ch's buffer
