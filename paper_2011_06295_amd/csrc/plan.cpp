@@ -48,45 +48,46 @@ struct Cand {
 // Tile height in lattice rows for a window of `span` positions starting anywhere in a row.
 int tile_rows(int span, int Wp, int R, int S) { return (Wp - 1 + span - 1 + (R - 1) * Wp + S - 1) / Wp + 1; }
 
-// Rough time of one launch in CU clocks, from measurements on MI355X.
+// Rough time of one launch in CU clocks.  The structure follows measurements on
+// MI355X; the constants were fitted to the measured times of ~7000 launch
+// configurations of the 13 VGG-16 layers (batch 128, fp32).
 //  * A step (kBatch stored weights of one output channel, for the 64 positions of
 //    a wavefront) costs its SIMD kBatch * (V + 1) vector instructions of ~4 clocks
 //    (fp16: the mixed-precision multiply-add takes ~4.4) and the CU's LDS
 //    kBatch * 64 elements at ~200 B/clk.  For 16-byte fp32 elements the two are
-//    equal, and when both are needed at full rate neither is reached: the inner
-//    loop was measured at ~61 % of either.
-//  * A lone wavefront cannot overlap its own LDS latency (~170 clocks a step).
-//  * Registers allow 20 resident wavefronts per CU up to KW = 2, 16 above.
+//    about equal, and they overlap only in part.
+//  * The wavefronts of a CU are spread over 4 SIMDs: the fullest SIMD sets the pace.
+//  * A lone wavefront cannot hide its own LDS and scalar-fetch latency (~300 clocks a step).
+//  * Registers allow 16 resident wavefronts per CU.
 //  * Staging moves ~16 B/clk/CU from L2 and overlaps the arithmetic except for the
-//    first chunk; a workgroup costs ~3 us to start and finish.
+//    first chunk; a workgroup costs ~2 us to start and finish.
 //  * Workgroups run in rounds of (CUs * resident workgroups); a partly filled
 //    last round still takes a round.
 double estimate(const Shape& s, const Cand& c)
 {
     const int nchunks = cdiv(s.C, c.Cc);
     const double seg = s.row_nnz * c.Cc / s.C;
-    const double batches = nchunks == 1 ? std::ceil(seg / kBatch) : seg / kBatch + 0.5;
+    const double batches = nchunks == 1 ? std::ceil(seg / kBatch) : seg / kBatch + 0.4;
     const double steps_wave = c.KW * batches * nchunks * 1.1;   // 10 %: wavefronts wait for the slowest at every chunk
     const int waves = c.WP * c.WK;
-    const int maxw = c.KW <= 2 ? 20 : 16;
-    const int conc_max = std::min(kMaxLds / c.lds, maxw / waves);
+    const int conc_max = std::min(kMaxLds / c.lds, kMaxWaves / waves);
     if (conc_max < 1) return -1.0;
     const long long wgs = (long long)cdiv(s.npos, (long long)kWave * c.WP) * cdiv(s.K, c.WK * c.KW);
     const double fma_clk = s.elem_bytes == 2 ? 4.4 : 4.0;
     const double v_step = kBatch * (c.V * fma_clk + 4.0);
     const double l_step = kBatch * 64.0 * s.ub / 200.0;
     const double gbytes = (double)s.C * c.CS * s.ub * ((double)s.W / s.Wp) * std::min(1.0, (double)s.H / s.Hs);
-    const double fixed = 7000.0 + 400.0 * nchunks;
+    const double fixed = 5000.0 + 400.0 * nchunks;
     double t = 0.0;
     long long remaining = wgs;
     const long long slots = (long long)kCUs * conc_max;
     while (remaining > 0) {
         const long long n = std::min(remaining, slots);
         const int conc = (int)((n + kCUs - 1) / kCUs);
-        const double W = (double)conc * waves;
+        const double W = 4.0 * cdiv((long long)conc * waves, 4);   // as if every SIMD were as full as the fullest
         const double a = W * v_step / 4.0, b = W * l_step;
-        const double shared = (std::max(a, b) + 0.5 * std::min(a, b)) / 0.92;
-        const double step_clk = std::max(shared, v_step + 170.0);
+        const double shared = (std::max(a, b) + 0.7 * std::min(a, b)) / 0.92;
+        const double step_clk = std::max(shared, v_step + 300.0);
         const double t_compute = steps_wave * step_clk;
         const double t_stage = conc * gbytes / 16.0;
         const long long full = remaining / slots;
