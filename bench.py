@@ -57,6 +57,10 @@ def layer_roofs(run, N, b):
     }
 
 
+# mean HBM-side bytes per launch of sc::tile_kernel (see profiles/)
+MEASURED_TRAFFIC = {"vgg16_f32": 28.0e6}
+
+
 def cpu_baseline(net, work, budget_s=12.0):
     """The oracle (float accumulation, one thread) on the first n images of every layer."""
     import oracle
@@ -93,6 +97,9 @@ def main():
     ap.add_argument("--workload", default="vgg16_f32")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--launch", default="", help="comma separated launch override applied to every layer")
+    ap.add_argument("--copy-probe-mib", type=int, default=0,
+                    help="after the timed steps, copy a device buffer of this size once (a kernel of known "
+                         "traffic that calibrates rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         raise SystemExit("bench.py: this build runs on one GPU only (the path shards by batch with no exchange "
@@ -150,6 +157,14 @@ def main():
                        if k in ("V", "WP", "WK", "KW", "Cc", "grid", "lds_bytes", "threads")},
         })
 
+    if args.copy_probe_mib > 0:
+        src = torch.empty(args.copy_probe_mib << 20, dtype=torch.uint8, device="cuda").random_(0, 255)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)      # reads and writes copy_probe_mib MiB
+        torch.cuda.synchronize()
+        del src, dst
+
     total_macs = net.total_macs()
     roofs = [layer_roofs(r, N, b) for r in net.runs]
     nl = len(net.runs)
@@ -162,7 +177,9 @@ def main():
         roofline = {"bound": "hbm", "achieved": sums["hbm_bytes"] / nl / avg_launch_s / 1e9, "peak": HBM_PEAK / 1e9,
                     "unit": "GB/s"}
     roofline["frac"] = roofline["achieved"] / roofline["peak"]
-    roofline["traffic"] = None
+    # HBM-side bytes per launch, measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE and scaled by a copy
+    # of known size (profiles/tile_kernel_*_hbm_traffic.md); null for workloads that were not profiled
+    roofline["traffic"] = MEASURED_TRAFFIC.get(args.workload)
     roofline["kernel"] = "sc::tile_kernel"
     roofline["avg_launch_us"] = avg_launch_s * 1e6
     roofline["launches_per_step"] = nl
