@@ -116,6 +116,30 @@ def test_degenerate_cases(dtype):
     check(w3, m3, x3, 2, 0, dtype, what="1x1")
 
 
+STAGING_CASES = [
+    # name, (N, C, K, R, S, H, W, stride, pad), launch override or None
+    ("tiny-maps-many-groups-per-tile", (37, 40, 24, 3, 3, 2, 2, 1, 1), [4, 1, 4, 1, 16, 0]),  # whole planes, channel-minor order
+    ("tiny-maps-automatic", (37, 40, 24, 3, 3, 2, 2, 1, 1), None),
+    ("4x4-maps-two-buffers", (29, 70, 20, 3, 3, 4, 4, 1, 1), [4, 1, 4, 2, 9, 0]),        # 8 chunks, ragged last chunk
+    ("rows-tile-spans-three-groups", (23, 12, 16, 3, 3, 8, 8, 1, 1), [4, 1, 3, 2, 5, 0]),
+    ("several-staging-passes", (3, 6, 10, 3, 3, 9, 70, 1, 1), [1, 1, 1, 2, 3, 0]),      # 64 threads, wide rows
+    ("several-passes-two-buffers-f16-wide", (9, 9, 8, 5, 5, 12, 50, 1, 2), [2, 1, 2, 1, 4, 0]),
+    ("one-image-per-element", (5, 7, 9, 3, 3, 10, 10, 1, 1), [1, 2, 2, 2, 0, 0]),
+    ("stride-2-pad-2", (6, 5, 12, 3, 3, 11, 13, 2, 2), [2, 1, 5, 1, 2, 0]),
+    ("single-chunk-single-buffer", (8, 3, 16, 3, 3, 16, 16, 1, 1), None),
+]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+@pytest.mark.parametrize("case", STAGING_CASES, ids=lambda c: c[0])
+def test_staging_modes(case, dtype):
+    """Slot orders (rows / whole planes), one or two tile buffers, one or several staging passes."""
+    name, (N, C, K, R, S, H, W, st, p), launch = case
+    rng = np.random.default_rng(len(name) * 1000 + N)
+    w, m, x = rand_layer(rng, N, C, K, R, S, H, W, density=0.3)
+    check(w, m, x, st, p, dtype, launch=launch, what=f"{name}-{dtype}")
+
+
 def test_hand_examples_on_gpu():
     import json
     import os
