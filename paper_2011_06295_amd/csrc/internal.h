@@ -47,7 +47,7 @@ struct Geometry {
 };
 
 constexpr int kStage = 4;  // tile elements a thread stages per chunk (loads in flight: kStage * V)
-constexpr int kBatch = 8;  // plan entries fetched per scalar load; segments are padded to a multiple
+constexpr int kBatch = 4;  // plan entries fetched per scalar load; segments are padded to a multiple
 
 // One stored weight as the kernel consumes it: fp32 weight bits and the LDS
 // byte offset ((c_local * CS + r * Wp + s) * element bytes) of its tap relative

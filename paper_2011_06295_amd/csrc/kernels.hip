@@ -17,7 +17,7 @@
 // on padding compute a value nobody stores.  A wavefront owns KW output
 // channels whose accumulators stay in registers across the channel chunks.
 // Stored weights arrive as (weight, LDS offset) pairs, wave-uniform, fetched in
-// batches of kBatch through the scalar path with one batch of look-ahead; per
+// batches of kBatch through the scalar path, a batch ahead of their use; per
 // pair a lane does one vector LDS read and V fused multiply-adds in fp32.
 #include <hip/hip_runtime.h>
 
@@ -345,10 +345,10 @@ __global__ __launch_bounds__(1024) void tile_kernel(const KernelArgs a)
     // finds them complete, and one wait serves LDS and scalar returns alike.
     // Entry offsets are in bytes: one VOP2 add per read.
     constexpr int kHalf = kBatch / 2;
-    static_assert(kHalf == 4, "arrived() names four registers");
-    // an empty statement that uses a half's registers: the compiler has to complete their loads before it
+    // empty statements that use a half's registers: the compiler has to complete their loads before them
     auto arrived = [](const vec(&x)[kHalf]) __attribute__((always_inline)) {
-        asm volatile("" ::"v"(x[0]), "v"(x[1]), "v"(x[2]), "v"(x[3]));
+#pragma unroll
+        for (int u = 0; u < kHalf; ++u) asm volatile("" ::"v"(x[u]));
     };
     auto compute = [&](int base, bool prefetch) __attribute__((always_inline)) {
         vec xa[kHalf], xb[kHalf];

@@ -49,8 +49,9 @@ struct Cand {
 int tile_rows(int span, int Wp, int R, int S) { return (Wp - 1 + span - 1 + (R - 1) * Wp + S - 1) / Wp + 1; }
 
 // Rough time of one launch in CU clocks.  The structure follows measurements on
-// MI355X; the constants were fitted to the measured times of ~7000 launch
-// configurations of the 13 VGG-16 layers (batch 128, fp32).
+// MI355X; the constants were fitted to the measured times of ~11000 launch
+// configurations of the 13 VGG-16 layers (batch 128, fp32) and of the 256->256
+// 14x14 layer at 50..99 % sparsity (batch 256).
 //  * A step (kBatch stored weights of one output channel, for the 64 positions of
 //    a wavefront) costs its SIMD kBatch * (V + 1) vector instructions of ~4 clocks
 //    (fp16: the mixed-precision multiply-add takes ~4.4) and the CU's LDS
@@ -59,8 +60,8 @@ int tile_rows(int span, int Wp, int R, int S) { return (Wp - 1 + span - 1 + (R -
 //  * The wavefronts of a CU are spread over 4 SIMDs: the fullest SIMD sets the pace.
 //  * A lone wavefront cannot hide its own LDS and scalar-fetch latency (~300 clocks a step).
 //  * Registers allow 16 resident wavefronts per CU.
-//  * Staging moves ~16 B/clk/CU from L2 and overlaps the arithmetic except for the
-//    first chunk; a workgroup costs ~2 us to start and finish.
+//  * Staging moves ~32 B/clk/CU from L2 and overlaps the arithmetic except for the
+//    first chunk; a workgroup costs ~7 us to start and finish.
 //  * Workgroups run in rounds of (CUs * resident workgroups); a partly filled
 //    last round still takes a round.
 double estimate(const Shape& s, const Cand& c)
@@ -68,7 +69,8 @@ double estimate(const Shape& s, const Cand& c)
     const int nchunks = cdiv(s.C, c.Cc);
     const double seg = s.row_nnz * c.Cc / s.C;
     const double batches = nchunks == 1 ? std::ceil(seg / kBatch) : seg / kBatch + 0.4;
-    const double steps_wave = c.KW * batches * nchunks * 1.1;   // 10 %: wavefronts wait for the slowest at every chunk
+    // 16 accumulator rows per wavefront spill registers: ~10 % slower steps
+    const double steps_wave = c.KW * batches * nchunks * (c.KW * c.V >= 64 ? 1.1 : 1.0);
     const int waves = c.WP * c.WK;
     const int conc_max = std::min(kMaxLds / c.lds, kMaxWaves / waves);
     if (conc_max < 1) return -1.0;
@@ -77,7 +79,7 @@ double estimate(const Shape& s, const Cand& c)
     const double v_step = kBatch * (c.V * fma_clk + 4.0);
     const double l_step = kBatch * 64.0 * s.ub / 200.0;
     const double gbytes = (double)s.C * c.CS * s.ub * ((double)s.W / s.Wp) * std::min(1.0, (double)s.H / s.Hs);
-    const double fixed = 5000.0 + 400.0 * nchunks;
+    const double fixed = 16000.0 + 400.0 * nchunks;
     double t = 0.0;
     long long remaining = wgs;
     const long long slots = (long long)kCUs * conc_max;
@@ -86,10 +88,10 @@ double estimate(const Shape& s, const Cand& c)
         const int conc = (int)((n + kCUs - 1) / kCUs);
         const double W = 4.0 * cdiv((long long)conc * waves, 4);   // as if every SIMD were as full as the fullest
         const double a = W * v_step / 4.0, b = W * l_step;
-        const double shared = (std::max(a, b) + 0.7 * std::min(a, b)) / 0.92;
+        const double shared = std::max(a, b) + 0.7 * std::min(a, b);
         const double step_clk = std::max(shared, v_step + 300.0);
         const double t_compute = steps_wave * step_clk;
-        const double t_stage = conc * gbytes / 16.0;
+        const double t_stage = conc * gbytes / 32.0;
         const long long full = remaining / slots;
         const double round = std::max(t_compute, t_stage) + t_stage / nchunks + fixed;
         if (full > 1) {            // identical full rounds
