@@ -31,6 +31,7 @@ class Network:
 
     def __init__(self, work: wl.Workload, unify: bool = False, layer_ids: Optional[List[int]] = None):
         self.work = work
+        self.layer_ids = layer_ids
         self.runs: List[LayerRun] = []
         self.host_weights = []
         for li, spec in enumerate(work.layers, 1):
@@ -60,7 +61,11 @@ class Network:
         """Pushes x0 through every layer once, keeping each layer's input and output on the device."""
         import torch
         x = torch.from_numpy(x0).cuda().to(self.torch_dtype()).contiguous()
-        for run in self.runs:
+        for li, run in enumerate(self.runs, 1):
+            if not self.work.chain and li > 1:   # independent layers: each has its own seeded input
+                lid = self.layer_ids[li - 1] if self.layer_ids else li
+                xi = wl.make_layer_input(self.work.config, lid, run.spec, self.work.N, self.work.input_dist)
+                x = torch.from_numpy(xi).cuda().to(self.torch_dtype()).contiguous()
             run.x = x
             run.y = run.layer.forward(x, run.spec.stride, run.spec.pad)
             x = self.glue(run.spec, run.y)

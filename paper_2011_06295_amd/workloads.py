@@ -80,6 +80,7 @@ class Workload:
     dtype: str  # "f32" | "f16"
     input_dist: str  # "uniform01" | "normal"
     layers: List[LayerSpec] = field(default_factory=list)
+    chain: bool = True  # False: independent layers, each with its own input (make_layer_input)
 
 
 # --------------------------------------------------------------------------
@@ -245,3 +246,41 @@ def sweep_layer(sparsity_bp: int, ragged: bool, N: int = 256) -> Workload:
 def sweep_layer_index(sparsity_bp: int, ragged: bool) -> int:
     """Layer number used for seeding a sweep point (1-based, unified then ragged)."""
     return 1 + SWEEP_SPARSITIES_BP.index(sparsity_bp) + (len(SWEEP_SPARSITIES_BP) if ragged else 0)
+
+
+# --------------------------------------------------------------------------
+# 1x1 and 1-D layers (the paper's ResNet / DenseNet bottlenecks and its
+# CNN-non-static text model); independent layers, not a chain
+# --------------------------------------------------------------------------
+
+def resnet_1x1(N: int = 128, dtype: str = "f32") -> Workload:
+    """The two ResNet-50 bottleneck 1x1 layers of the paper's result tables ("256 filters
+    1x1x64" and "64 filters 1x1x256"), 90 % unified sparsity, on 56x56 maps (the
+    ImageNet-sized stage those filter counts belong to)."""
+    return Workload(f"resnet_1x1_{dtype}", 6, N, dtype, "normal", [
+        LayerSpec("res_256f_1x1x64", C=64, K=256, R=1, S=1, H=56, W=56, pad=0, sparsity_bp=9000),
+        LayerSpec("res_64f_1x1x256", C=256, K=64, R=1, S=1, H=56, W=56, pad=0, sparsity_bp=9000),
+    ], chain=False)
+
+
+def densenet_1x1(N: int = 128, dtype: str = "f32") -> Workload:
+    """The DenseNet 1x1 bottleneck layers of the paper's table: input channels are the block
+    input plus (layer - 1) * growth, output 4 * growth, at the block's map size."""
+    return Workload(f"densenet_1x1_{dtype}", 7, N, dtype, "normal", [
+        LayerSpec("dn121_b3_l24_87", C=256 + 23 * 32, K=128, R=1, S=1, H=14, W=14, pad=0, sparsity_bp=8750),
+        LayerSpec("dn121_b3_l24_91", C=256 + 23 * 32, K=128, R=1, S=1, H=14, W=14, pad=0, sparsity_bp=9100),
+        LayerSpec("dn161_b4_l16_91", C=1056 + 15 * 48, K=192, R=1, S=1, H=7, W=7, pad=0, sparsity_bp=9100),
+        LayerSpec("dn161_b3_l16_93", C=384 + 15 * 48, K=192, R=1, S=1, H=14, W=14, pad=0, sparsity_bp=9300),
+    ], chain=False)
+
+
+def cnn_1d(N: int = 128, dtype: str = "f32") -> Workload:
+    """1-D convolutions of the CNN-non-static text model: a sentence of 64 words with
+    300-dimensional embeddings is read as 300 channels of length 64 (H = 1), 100 filters
+    spanning 2 or 3 words, at the paper's three sparsity levels."""
+    layers = []
+    for ks in (2, 3):
+        for s_bp in (7700, 8300, 8750):
+            layers.append(LayerSpec(f"cnn1d_k{ks}_{s_bp // 100}", C=300, K=100, R=1, S=ks, H=1, W=64,
+                                    pad=0, sparsity_bp=s_bp))
+    return Workload(f"cnn_1d_{dtype}", 8, N, dtype, "normal", layers, chain=False)

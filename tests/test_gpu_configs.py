@@ -121,6 +121,25 @@ def test_config5_sweep_sampled(sparsity_bp, ragged):
     net.close()
 
 
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+@pytest.mark.parametrize("which", ["resnet_1x1", "densenet_1x1", "cnn_1d"])
+def test_1x1_and_1d_layers(which, dtype):
+    """The paper's 1x1 bottleneck and 1-D text-model layers: every element at batch 5, sampled at batch 128."""
+    from paper_2011_06295_amd import workloads as wl
+    for N, full in ((5, True), (128, False)):
+        work = getattr(wl, which)(N, dtype)
+        net = _net(work)
+        net.run_chain(wl.make_input(work))
+        for li, run in enumerate(net.runs):
+            what = f"{which}-{dtype}-N{N}-{run.spec.name}"
+            if full:
+                err = check_layer_full(run, net.host_weights[li], dtype, what)
+            else:
+                err = check_layer_sampled(run, net.host_weights[li], dtype, what, npts=1500, seed=li)
+            print(f"{what}: {run.layer.get_launch(N, run.spec.H, run.spec.W, 1, 0)} max err / max|ref| = {err:.3g}", flush=True)
+        net.close()
+
+
 def test_config5_unify_flag_matches_plain_rows():
     """Ragged rows padded to a unified count with explicit zeros give the same numbers."""
     import torch
