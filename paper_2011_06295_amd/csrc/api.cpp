@@ -209,6 +209,8 @@ int sparse_conv_forward(sparse_conv_t h, const void* input, void* output,
         a.fd_W = sc::make_fastdiv(W);
         a.fd_HW = sc::make_fastdiv(H * W);
         a.fd_SP = sc::make_fastdiv(p->SP);
+        a.pitch = p->pitch;
+        a.fd_pitch = sc::make_fastdiv(p->pitch);
 #ifdef SC_PHASE_TIMING
         a.phase = g_phase_buffer;
 #endif

@@ -86,7 +86,8 @@ struct Plan {
     int nbuf;      // tile buffers in LDS: 2 when there are several chunks
     int SL;        // staging slots per channel = SG * SP
     int SG, SP;    // slot groups and slots per group
-    int rows_mode; // staging slots enumerate tile rows instead of image groups
+    int rows_mode; // staging slots: 0 whole planes group by group, 1 tile rows, 2 every element of a banded tile
+    int pitch;     // row pitch inside the tile: Wp, or span + S - 1 for a banded tile
     int tbl_off;   // LDS byte offset of the slot table
     int lds_bytes; // tile + slot table
     int grid;      // workgroups launched (ntiles * kblocks rounded up to the XCD count)
@@ -130,12 +131,13 @@ struct KernelArgs {
     // ordered (group, channel, slot-in-group) and a thread's next unit is nthreads further on
     int SL;          // slots of one channel
     int SG, SP;      // rows mode: 1 group of Hb*W slots; groups mode: GC image groups of H*W slots
-    int rows_mode;   // slots enumerate tile rows (Hs >= Hb) instead of image groups
+    int rows_mode;   // slots: 0 whole planes group by group, 1 tile rows, 2 every element of a banded tile
+    int pitch;       // banded tile: elements per band (span + S - 1)
     int tbl_off;     // byte offset of the slot table in LDS (after the tile)
     int st_dg, st_dc, st_dp; // nthreads = st_dg * (Cc * SP) + st_dc * SP + st_dp
     int nbuf;                // tile buffers in LDS: 2 when there are several chunks
     int npass;               // staging passes per chunk: ceil(SG * Cc * SP / (kStage * threads))
-    FastDiv fd_Wp, fd_Hs, fd_W, fd_HW, fd_SP, fd_CP;  // divisors Wp, Hs, W, H*W, SP, Cc*SP
+    FastDiv fd_Wp, fd_Hs, fd_W, fd_HW, fd_SP, fd_CP, fd_pitch;  // divisors Wp, Hs, W, H*W, SP, Cc*SP, pitch
 #ifdef SC_PHASE_TIMING
     unsigned long long* phase;  // 8 counters per workgroup, or null
 #endif

@@ -133,10 +133,12 @@ __global__ __launch_bounds__(1024) void tile_kernel(const KernelArgs a)
     const int lq0 = (int)q0 - Y0 * a.Wp;
 
     // lane -> position -> output element (if any)
-    const int lpos = lq0 + wp * 64 + lane;      // tile-local element index of the position
+    const int lrel = lq0 + wp * 64 + lane;      // position relative to the start of lattice row Y0
+    // tile element of the position: the tile starts at that row, or (banded tile) at the first position
+    const int lpos = a.rows_mode == 2 ? wp * 64 + lane : lrel;
     const int lposb = lpos * (int)sizeof(vec);
-    const int Yl = fdiv(lpos, a.fd_Wp);
-    const int X = lpos - Yl * a.Wp;
+    const int Yl = fdiv(lrel, a.fd_Wp);
+    const int X = lrel - Yl * a.Wp;
     const int Y = Y0 + Yl;
     const int g = fdiv(Y, a.fd_Hs);
     const int yy = Y - g * a.Hs;
@@ -230,7 +232,15 @@ __global__ __launch_bounds__(1024) void tile_kernel(const KernelArgs a)
     int2* tbl = reinterpret_cast<int2*>(smem + a.tbl_off);
     for (int sl = tid; sl < a.SL; sl += nthreads) {
         int gs, ys, xx, Yt;
-        if (a.rows_mode) {
+        if (a.rows_mode == 2) {  // banded tile: element sl is lattice element q0 + band * Wp + offset
+            const int band = fdiv(sl, a.fd_pitch);
+            const int Ls = (int)q0 + band * a.Wp + (sl - band * a.pitch);
+            const int Ys = fdiv(Ls, a.fd_Wp);
+            gs = fdiv(Ys, a.fd_Hs);
+            ys = Ys - gs * a.Hs - a.pad;
+            xx = Ls - Ys * a.Wp - a.pad;
+            Yt = 0;
+        } else if (a.rows_mode) {
             Yt = fdiv(sl, a.fd_W);
             xx = sl - Yt * a.W;
             const int Ys = Y0 + Yt;
@@ -244,12 +254,12 @@ __global__ __launch_bounds__(1024) void tile_kernel(const KernelArgs a)
             gs = g_first + gi;
             Yt = gs * a.Hs + a.pad + ys - Y0;
         }
-        const bool ok = gs < a.ngroups && ys >= 0 && ys < a.H && Yt >= 0 && Yt < a.Hb;
+        const bool ok = gs < a.ngroups && ys >= 0 && ys < a.H && xx >= 0 && xx < a.W && Yt >= 0 && Yt < a.Hb;
         int2 t;
         // (gs - g_first) * V * img_bytes < 2^31 is guaranteed by the host
         t.x = ok ? (int)((unsigned)((gs - g_first) * V) * img_bytes + (unsigned)(ys * a.W + xx) * (unsigned)sizeof(T))
                  : (int)0x80000000;
-        t.y = ok ? Yt * a.Wp + a.pad + xx : 0;
+        t.y = !ok ? 0 : a.rows_mode == 2 ? sl : Yt * a.Wp + a.pad + xx;
         tbl[sl] = t;
     }
     // A chunk is SG * Cc * SP units, unit u = (slot group * Cc + channel) * SP + slot: in that

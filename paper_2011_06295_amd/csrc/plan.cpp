@@ -42,7 +42,7 @@ struct Shape {
 
 struct Cand {
     int V, WP, WK, KW, Cc;
-    int Hb, CS, lds, SL, rows_mode, SG, nbuf;
+    int Hb, CS, lds, SL, rows_mode, SG, nbuf, pitch;
 };
 
 // Tile height in lattice rows for a window of `span` positions starting anywhere in a row.
@@ -157,7 +157,7 @@ int build_plan(const Csr& csr, int C, int R, int S, int elem_bytes, const Geomet
         const int ngroups = std::max(1, cdiv(g.N, V));
         s.npos = (long long)ngroups * s.Hs * s.Wp;
         s.row_nnz = K > 0 ? (double)csr.colidx.size() / K : 0.0;
-        if (s.npos + 1024 >= (1ll << 31)) {  // positions are 32-bit in the kernel
+        if (s.npos + (long long)(R + 1) * s.Wp + 2048 >= (1ll << 31)) {  // lattice elements are 32-bit in the kernel
             too_many_positions = true;
             continue;
         }
@@ -165,12 +165,20 @@ int build_plan(const Csr& csr, int C, int R, int S, int elem_bytes, const Geomet
             if (over.WP && WP != 1) break;
             const int wp = over.WP ? over.WP : WP;
             const int Hb = tile_rows(kWave * wp, s.Wp, R, S);
-            const long long CS = (long long)Hb * s.Wp;
-            // staging slots per channel: the tile's rows, or (small maps) the whole planes of every group it can touch
+            // Tile layout per channel.  Contiguous: the Hb lattice rows the positions and their taps
+            // touch, pitch Wp.  Banded (maps much wider than the tile): R bands of span + S - 1
+            // consecutive lattice elements, band r starting r rows below the first position.
+            const int P2 = kWave * wp + S - 1;
+            const bool banded = (long long)R * P2 < (long long)Hb * s.Wp;
+            const long long CS = banded ? (long long)R * P2 : (long long)Hb * s.Wp;
+            const int pitch = banded ? P2 : s.Wp;
+            // staging slots per channel: every tile element (banded), the tile's rows, or (small maps)
+            // the whole planes of every group it can touch
             // (whole planes only where a plane is a short run of memory: the order then continues across channels)
-            const long long GC = (Hb + s.Hs - 2) / s.Hs + 1;      // image groups a tile can touch
-            const bool rows_mode = s.Hs >= Hb || (long long)g.H * g.W * elem_bytes >= 128;
-            const long long SL = rows_mode ? (long long)Hb * g.W : GC * g.H * g.W;
+            const int rows_spanned = banded ? (R - 1) + (P2 + s.Wp - 1) / s.Wp + 1 : Hb;
+            const long long GC = (rows_spanned + s.Hs - 2) / s.Hs + 1;      // image groups a tile can touch
+            const bool rows_mode = banded || s.Hs >= Hb || (long long)g.H * g.W * elem_bytes >= 128;
+            const long long SL = banded ? CS : rows_mode ? (long long)Hb * g.W : GC * g.H * g.W;
             const long long tbl = SL * 8;
             // slot offsets are 31-bit byte offsets from the first image group of a tile
             if (GC * V * C * g.H * g.W * elem_bytes >= (1ll << 31)) continue;
@@ -205,7 +213,7 @@ int build_plan(const Csr& csr, int C, int R, int S, int elem_bytes, const Geomet
                         // tile buffer(s), one reject element, table
                         const long long lds = (((long long)nbuf * Cc * CS + 1) * s.ub + 15) / 16 * 16 + tbl;
                         if (lds > kMaxLds) continue;
-                        Cand c{V, wp, wk, kw, Cc, Hb, (int)CS, (int)lds, (int)SL, rows_mode ? 1 : 0, rows_mode ? 1 : (int)GC, nbuf};
+                        Cand c{V, wp, wk, kw, Cc, Hb, (int)CS, (int)lds, (int)SL, banded ? 2 : rows_mode ? 1 : 0, rows_mode ? 1 : (int)GC, nbuf, pitch};
                         double t = estimate(s, c);
                         if (t < 0) {
                             if (!(over.WP || over.WK || over.KW || over.Cc || over.lds_budget)) continue;
@@ -243,6 +251,7 @@ int build_plan(const Csr& csr, int C, int R, int S, int elem_bytes, const Geomet
     p.SG = best.SG;
     p.SP = best.SL / best.SG;
     p.rows_mode = best.rows_mode;
+    p.pitch = best.pitch;
     p.nbuf = best.nbuf;
     p.tbl_off = ((p.nbuf * p.Cc * p.CS + 1) * s.ub + 15) / 16 * 16;
     const long long grid = (ntiles * p.kblocks + 7) / 8 * 8;   // a multiple of the XCD count
@@ -282,7 +291,7 @@ int build_plan(const Csr& csr, int C, int R, int S, int elem_bytes, const Geomet
                         const float wv = csr.val32[(size_t)(q - csr.colidx.data())];
                         uint32_t wb;
                         __builtin_memcpy(&wb, &wv, 4);
-                        last = Entry{wb, ((c - c0) * p.CS + r * p.Wp + sx) * s.ub};
+                        last = Entry{wb, ((c - c0) * p.CS + r * p.pitch + sx) * s.ub};
                         p.entries.push_back(last);
                     }
                     const int nb = cdiv(n, kBatch);

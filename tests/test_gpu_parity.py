@@ -127,6 +127,12 @@ STAGING_CASES = [
     ("one-image-per-element", (5, 7, 9, 3, 3, 10, 10, 1, 1), [1, 2, 2, 2, 0, 0]),
     ("stride-2-pad-2", (6, 5, 12, 3, 3, 11, 13, 2, 2), [2, 1, 5, 1, 2, 0]),
     ("single-chunk-single-buffer", (8, 3, 16, 3, 3, 16, 16, 1, 1), None),
+    # maps much wider than a tile: banded tile layout (positions of a tile wrap over lattice rows)
+    ("banded-3x3-wide", (3, 5, 7, 3, 3, 9, 150, 1, 1), [4, 1, 2, 2, 2, 0]),
+    ("banded-1x1-56x56", (5, 24, 16, 1, 1, 56, 56, 1, 0), None),
+    ("banded-5x5-two-position-waves", (2, 4, 6, 5, 5, 40, 300, 1, 2), [2, 2, 2, 1, 3, 0]),
+    ("banded-stride-2", (6, 3, 9, 3, 3, 31, 200, 2, 1), [4, 1, 3, 1, 0, 0]),
+    ("banded-1d", (7, 20, 10, 1, 3, 1, 500, 1, 0), None),
 ]
 
 
