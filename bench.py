@@ -36,7 +36,8 @@ def make_workload(name: str):
         return wl.lenet5(64), None
     if name == "config1":
         return wl.config1(), None
-    for base, fn in (("resnet1x1", wl.resnet_1x1), ("densenet1x1", wl.densenet_1x1), ("cnn1d", wl.cnn_1d)):
+    for base, fn in (("resnet1x1", wl.resnet_1x1), ("densenet1x1", wl.densenet_1x1), ("cnn1d", wl.cnn_1d),
+                     ("vgg16_224", wl.vgg16_imagenet)):
         if name in (base, base + "_f16"):
             return fn(128, "f16" if name.endswith("_f16") else "f32"), None
     if name.startswith("sweep"):      # sweep90, sweep95r (r = ragged rows)

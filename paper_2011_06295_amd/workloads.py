@@ -284,3 +284,15 @@ def cnn_1d(N: int = 128, dtype: str = "f32") -> Workload:
             layers.append(LayerSpec(f"cnn1d_k{ks}_{s_bp // 100}", C=300, K=100, R=1, S=ks, H=1, W=64,
                                     pad=0, sparsity_bp=s_bp))
     return Workload(f"cnn_1d_{dtype}", 8, N, dtype, "normal", layers, chain=False)
+
+
+VGG_IMAGENET_LAYERS = [(3, 224, 64), (64, 224, 64), (64, 112, 128), (128, 112, 128), (128, 56, 256),
+                       (256, 56, 256), (256, 28, 512), (512, 28, 512), (512, 14, 512)]
+
+
+def vgg16_imagenet(N: int = 128, dtype: str = "f32") -> Workload:
+    """The nine distinct 3x3 layer shapes (C, H = W, K) of VGG-16 on 224x224 images that the
+    paper's timing table lists, each at 90 % unified sparsity; independent layers."""
+    return Workload(f"vgg16_224px_{dtype}", 9, N, dtype, "normal", [
+        LayerSpec(f"{c}x{hw}x{hw}x{k}", C=c, K=k, R=3, S=3, H=hw, W=hw, stride=1, pad=1, sparsity_bp=9000)
+        for (c, hw, k) in VGG_IMAGENET_LAYERS], chain=False)

@@ -140,6 +140,20 @@ def test_1x1_and_1d_layers(which, dtype):
         net.close()
 
 
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+def test_imagenet_sized_vgg_layers_sampled(dtype):
+    """The paper's nine 224-pixel VGG layer shapes at batch 6 (banded tiles, partial last image group)."""
+    from paper_2011_06295_amd import workloads as wl
+    work = wl.vgg16_imagenet(6, dtype)
+    net = _net(work)
+    net.run_chain(wl.make_input(work))
+    for li, run in enumerate(net.runs):
+        what = f"vgg224-{dtype}-{run.spec.name}"
+        err = check_layer_sampled(run, net.host_weights[li], dtype, what, npts=1500, seed=li)
+        print(f"{what}: {run.layer.get_launch(6, run.spec.H, run.spec.W, 1, 1)} max err / max|ref| = {err:.3g}", flush=True)
+    net.close()
+
+
 def test_config5_unify_flag_matches_plain_rows():
     """Ragged rows padded to a unified count with explicit zeros give the same numbers."""
     import torch
