@@ -174,7 +174,12 @@ def main():
     nl = len(net.runs)
     avg_launch_s = gpu_ms * 1e-3 / (args.steps * nl)
     sums = {k: sum(rf[k] for rf in roofs) for k in ("t_hbm", "t_lds", "t_valu", "lds_bytes", "hbm_bytes")}
-    if sums["t_lds"] >= sums["t_hbm"]:
+    # the binding roof is the largest of the three times (fp32: LDS and VALU tie, reported as LDS;
+    # fp16: half the LDS bytes per MAC, so the non-packed fp32 multiply-add rate binds)
+    if sums["t_valu"] > sums["t_lds"] and sums["t_valu"] >= sums["t_hbm"]:
+        roofline = {"bound": "alu", "achieved": 2.0 * total_macs / nl / avg_launch_s / 1e12,
+                    "peak": 2.0 * VALU_PEAK_FMA / 1e12, "unit": "TFLOP/s"}
+    elif sums["t_lds"] >= sums["t_hbm"]:
         roofline = {"bound": "lds", "achieved": sums["lds_bytes"] / nl / avg_launch_s / 1e9, "peak": LDS_PEAK / 1e9,
                     "unit": "GB/s"}
     else:
