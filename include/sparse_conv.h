@@ -42,6 +42,9 @@ enum { SC_F32 = 0, SC_F16 = 1 };
  * the fullest row, so all output channels have one unified count. */
 enum { SC_FLAG_UNIFY_NNZ = 1u };
 
+/* Epilogue flag: apply ReLU to the stored value (sparse_conv_set_epilogue). */
+enum { SC_EPILOGUE_RELU = 1u };
+
 /*
  * sparse_conv_create - build the CSR form of one pruned layer (section 7).
  *   out      receives the handle.
@@ -114,6 +117,19 @@ int sparse_conv_get_csr(sparse_conv_t h, int* K, long long* nnz,
  * kernels cannot run; a configuration that cannot fit is reported by forward.
  */
 int sparse_conv_set_launch(sparse_conv_t h, const int* params, int nparams);
+
+/*
+ * sparse_conv_set_epilogue - what the store step does with a finished sum
+ * (section 3: the sum over the filter is added to the bias of its output channel
+ * and the activation function is applied).  Default: store the bare sum.
+ *   bias   HOST, fp32 [K], added to every output element of channel k before
+ *          anything else; NULL = no bias.  Copied by the call (one synchronous
+ *          device allocation and copy).
+ *   flags  0 or SC_EPILOGUE_RELU: out = max(sum + bias, 0).
+ * For SC_F16 the fp32 value is rounded to binary16 once, after bias and ReLU.
+ * Applies to every later forward of this handle.
+ */
+int sparse_conv_set_epilogue(sparse_conv_t h, const float* bias, unsigned flags);
 
 /* The launch configuration chosen for a geometry, in the order of
  * sparse_conv_set_launch, followed by [6] workgroups launched, [7] LDS bytes

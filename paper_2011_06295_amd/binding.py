@@ -16,6 +16,7 @@ import numpy as np
 SC_OK, SC_EINVAL, SC_EUNSUPPORTED, SC_ENOMEM, SC_EHIP = 0, -1, -2, -3, -4
 SC_F32, SC_F16 = 0, 1
 SC_FLAG_UNIFY_NNZ = 1
+SC_EPILOGUE_RELU = 1
 
 # SPARSECONV_LIBRARY names another build of the same library (e.g. an instrumented one)
 LIB_PATH = os.environ.get("SPARSECONV_LIBRARY") or os.path.join(
@@ -23,7 +24,7 @@ LIB_PATH = os.environ.get("SPARSECONV_LIBRARY") or os.path.join(
 
 EXPORTS = (
     "sparse_conv_create", "sparse_conv_output_shape", "sparse_conv_forward",
-    "sparse_conv_get_csr", "sparse_conv_set_launch", "sparse_conv_get_launch",
+    "sparse_conv_get_csr", "sparse_conv_set_launch", "sparse_conv_get_launch", "sparse_conv_set_epilogue",
     "sparse_conv_last_hip_error", "sparse_conv_strerror", "sparse_conv_destroy",
 )
 
@@ -53,6 +54,7 @@ def _load():
     lib.sparse_conv_get_csr.argtypes = [vp, ip, C.POINTER(C.c_longlong), C.POINTER(vp), C.POINTER(vp), C.POINTER(vp)]
     lib.sparse_conv_set_launch.argtypes = [vp, ip, C.c_int]
     lib.sparse_conv_get_launch.argtypes = [vp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, ip]
+    lib.sparse_conv_set_epilogue.argtypes = [vp, vp, C.c_uint]
     lib.sparse_conv_last_hip_error.argtypes = [vp]
     lib.sparse_conv_strerror.argtypes = [C.c_int]
     lib.sparse_conv_strerror.restype = C.c_char_p
@@ -127,6 +129,13 @@ def sparse_conv_set_launch(handle: int, params: Sequence[int]) -> None:
     _check(_lib.sparse_conv_set_launch(handle, arr, len(params)), "sparse_conv_set_launch", handle)
 
 
+def sparse_conv_set_epilogue(handle: int, bias: Optional[np.ndarray], flags: int = 0) -> None:
+    """bias: HOST fp32 [K] or None; flags: 0 or SC_EPILOGUE_RELU."""
+    b = None if bias is None else np.ascontiguousarray(bias, dtype=np.float32)
+    ptr = None if b is None else b.ctypes.data_as(C.c_void_p)
+    _check(_lib.sparse_conv_set_epilogue(handle, ptr, C.c_uint(flags)), "sparse_conv_set_epilogue", handle)
+
+
 def sparse_conv_get_launch(handle: int, N: int, H: int, W: int, stride: int, pad: int) -> dict:
     arr = (C.c_int * 10)()
     _check(_lib.sparse_conv_get_launch(handle, N, H, W, stride, pad, arr), "sparse_conv_get_launch", handle)
@@ -161,6 +170,9 @@ class SparseConv:
 
     def set_launch(self, params: Sequence[int]):
         sparse_conv_set_launch(self.handle, params)
+
+    def set_epilogue(self, bias: Optional[np.ndarray] = None, relu: bool = False):
+        sparse_conv_set_epilogue(self.handle, bias, SC_EPILOGUE_RELU if relu else 0)
 
     def get_launch(self, N, H, W, stride=1, pad=0):
         return sparse_conv_get_launch(self.handle, N, H, W, stride, pad)

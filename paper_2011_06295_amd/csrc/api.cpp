@@ -142,6 +142,25 @@ int sparse_conv_set_launch(sparse_conv_t h, const int* params, int nparams)
     return SC_OK;
 }
 
+int sparse_conv_set_epilogue(sparse_conv_t h, const float* bias, unsigned flags)
+{
+    if (!h || (flags & ~static_cast<unsigned>(SC_EPILOGUE_RELU))) return SC_EINVAL;
+    float* d = nullptr;
+    if (bias) {
+        hipError_t e = hipMalloc(reinterpret_cast<void**>(&d), sizeof(float) * (size_t)h->K);
+        if (e == hipSuccess) e = hipMemcpy(d, bias, sizeof(float) * (size_t)h->K, hipMemcpyHostToDevice);
+        if (e != hipSuccess) {
+            h->last_hip = (int)e;
+            if (d) (void)hipFree(d);
+            return e == hipErrorOutOfMemory ? SC_ENOMEM : SC_EHIP;
+        }
+    }
+    if (h->d_bias) (void)hipFree(h->d_bias);
+    h->d_bias = d;
+    h->epilogue = flags;
+    return SC_OK;
+}
+
 int sparse_conv_get_launch(sparse_conv_t h, int N, int H, int W, int stride, int pad, int* params)
 {
     if (!h || !params || N < 0) return SC_EINVAL;
@@ -185,6 +204,8 @@ int sparse_conv_forward(sparse_conv_t h, const void* input, void* output,
         a.entries = static_cast<const sc::Entry*>(p->d_entries);
         a.seg = static_cast<const int*>(p->d_seg);
         a.krow = static_cast<const int*>(p->d_krow);
+        a.bias = h->d_bias;
+        a.relu = (h->epilogue & SC_EPILOGUE_RELU) ? 1 : 0;
         a.N = N; a.C = h->C; a.H = H; a.W = W; a.K = h->K; a.E = p->E; a.F = p->F;
         a.stride = stride; a.pad = pad;
         a.WP = p->WP; a.WK = p->WK; a.Cc = p->Cc;
@@ -241,6 +262,10 @@ const char* sparse_conv_strerror(int code)
     return "unknown status";
 }
 
-void sparse_conv_destroy(sparse_conv_t h) { delete h; }
+void sparse_conv_destroy(sparse_conv_t h)
+{
+    if (h && h->d_bias) (void)hipFree(h->d_bias);
+    delete h;
+}
 
 }  // extern "C"

@@ -123,6 +123,8 @@ struct KernelArgs {
     const Entry* entries;
     const int* seg;
     const int* krow;
+    const float* bias;   // [K] or null
+    int relu;            // clamp the stored value at zero
     int N, C, H, W, K, E, F, stride, pad;
     int WP, WK, Cc, Wp, Hs, Hb, CS, span;
     int nchunks, ngroups, ntiles, kblocks;
@@ -154,6 +156,8 @@ struct sparse_conv_s {
     unsigned flags;
     sc::Csr csr;
     sc::Launch over;
+    float* d_bias = nullptr;   // device copy of the epilogue bias (owned)
+    unsigned epilogue = 0;
     std::map<sc::Geometry, std::unique_ptr<sc::Plan>> plans;
     int last_hip = 0;
 };

@@ -467,10 +467,13 @@ __global__ __launch_bounds__(1024) void tile_kernel(const KernelArgs a)
         for (int kk = 0; kk < KW; ++kk) {
             const int k = kr[kk];
             if (k < 0) continue;
+            const float bias = a.bias ? as_constant(a.bias)[k] : 0.f;  // section 3: bias, then activation
 #pragma unroll
             for (int v = 0; v < V; ++v) {
                 const int n = g * V + v;
-                if (n < a.N) y[((size_t)n * a.K + k) * plane + pix] = (T)acc[kk][v];
+                float r = acc[kk][v] + bias;
+                if (a.relu) r = r > 0.f ? r : 0.f;
+                if (n < a.N) y[((size_t)n * a.K + k) * plane + pix] = (T)r;
             }
         }
     }

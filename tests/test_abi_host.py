@@ -93,6 +93,9 @@ def test_argument_validation_returns_status_codes():
     assert lib.sparse_conv_forward(h, None, None, 0, 8, 8, 1, 1, None) == B.SC_OK               # empty batch: no-op
     bad = (C.c_int * 6)(3, 0, 0, 0, 0, 0)
     assert lib.sparse_conv_set_launch(h, bad, 6) == B.SC_EINVAL                                  # V must be a power of two
+    assert lib.sparse_conv_set_epilogue(None, None, 0) == B.SC_EINVAL
+    assert lib.sparse_conv_set_epilogue(h, None, 2) == B.SC_EINVAL                               # unknown epilogue flag
+    assert lib.sparse_conv_set_epilogue(h, None, B.SC_EPILOGUE_RELU) == B.SC_OK                  # no bias: nothing to copy, needs no GPU
     assert lib.sparse_conv_strerror(B.SC_EINVAL) == b"invalid argument"
     lib.sparse_conv_destroy(h)
     lib.sparse_conv_destroy(None)

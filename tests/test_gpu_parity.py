@@ -146,6 +146,27 @@ def test_staging_modes(case, dtype):
     check(w, m, x, st, p, dtype, launch=launch, what=f"{name}-{dtype}")
 
 
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+def test_bias_and_relu_in_the_store_step(dtype):
+    """Section 3: the sum is added to the channel's bias, then the activation is applied."""
+    from paper_2011_06295_amd import binding as B
+    rng = np.random.default_rng(404)
+    N, C, K, R, S, H, W = 7, 9, 21, 3, 3, 12, 10
+    w, m, x = rand_layer(rng, N, C, K, R, S, H, W, density=0.3)
+    bias = rng.standard_normal(K).astype(np.float32)
+    conv = oracle_ref(w, m, x, 1, 1, dtype).astype(np.float64)
+    layer = B.SparseConv(w, m, dtype=dtype)
+    cases = [(None, False, conv), (bias, False, conv + bias[None, :, None, None]),
+             (None, True, np.maximum(conv, 0.0)), (bias, True, np.maximum(conv + bias[None, :, None, None], 0.0))]
+    for b, relu, ref in cases + cases[:1]:   # and back to the bare sum
+        layer.set_epilogue(b, relu)
+        got = run_gpu(layer, x, 1, 1, dtype)
+        assert_close(got, ref.astype(np.float32), TOL[dtype], f"epilogue-bias{b is not None}-relu{relu}-{dtype}")
+        if relu:
+            assert (got >= 0).all() and (got == 0).any()
+    layer.close()
+
+
 def test_hand_examples_on_gpu():
     import json
     import os
