@@ -101,6 +101,9 @@ def main():
     ap.add_argument("--workload", default="vgg16_f32")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--launch", default="", help="comma separated launch override applied to every layer")
+    ap.add_argument("--compare-dense", action="store_true",
+                    help="also time the platform's dense convolution (torch / MIOpen) per layer and report which "
+                         "of the two a dispatcher would pick")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="after the timed steps, copy a device buffer of this size once (a kernel of known "
                          "traffic that calibrates rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
@@ -208,6 +211,12 @@ def main():
         "roofline": roofline,
         "layers": layers,
     }
+    if args.compare_dense:
+        rows = net.compare_with_dense()
+        out["dense_comparison"] = {"layers": rows,
+                                   "sparse_us": round(sum(r["sparse_us"] for r in rows), 1),
+                                   "dense_us": round(sum(r["dense_us"] for r in rows), 1),
+                                   "dispatched_us": round(sum(min(r["sparse_us"], r["dense_us"]) for r in rows), 1)}
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(net, work)
     print(json.dumps(out))

@@ -77,6 +77,40 @@ class Network:
         for run in self.runs:
             run.layer.forward(run.x, run.spec.stride, run.spec.pad, out=run.y)
 
+    def compare_with_dense(self, reps: int = 20):
+        """Per layer: time of the sparse kernel and of the platform's dense convolution
+        (torch.nn.functional.conv2d, i.e. MIOpen) on the same masked weights and resident input,
+        and which of the two a dispatcher would pick (the paper's Algorithm 2 compares the
+        layers' efficiency once and routes each layer to the faster implementation).
+        Returns a list of dicts: name, sparse_us, dense_us, choice, max_abs_diff."""
+        import torch
+        import torch.nn.functional as F
+        out = []
+        for (w, m), run in zip(self.host_weights, self.runs):
+            s = run.spec
+            wd = torch.from_numpy(w * m).cuda().to(self.torch_dtype())
+            yd = F.conv2d(run.x, wd, None, s.stride, s.pad)
+            ys = run.layer.forward(run.x, s.stride, s.pad, out=run.y)
+            diff = float((yd.float() - ys.float()).abs().max())
+            times = {}
+            for name, fn in (("sparse", lambda: run.layer.forward(run.x, s.stride, s.pad, out=run.y)),
+                             ("dense", lambda: F.conv2d(run.x, wd, None, s.stride, s.pad))):
+                for _ in range(3):
+                    fn()
+                a, z = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record()
+                for _ in range(reps):
+                    fn()
+                z.record()
+                torch.cuda.synchronize()
+                times[name] = a.elapsed_time(z) * 1e3 / reps
+            out.append({"name": s.name, "sparsity": s.sparsity_bp / 100.0, "sparse_us": round(times["sparse"], 2),
+                        "dense_us": round(times["dense"], 2),
+                        "choice": "sparse" if times["sparse"] <= times["dense"] else "dense",
+                        "max_abs_diff": diff})
+            del wd, yd
+        return out
+
     def total_macs(self) -> int:
         return sum(r.macs(self.work.N) for r in self.runs)
 

@@ -154,6 +154,22 @@ def test_imagenet_sized_vgg_layers_sampled(dtype):
     net.close()
 
 
+def test_dense_comparison_routes_every_layer():
+    """The dense platform convolution on the masked weights gives the same numbers, and the
+    dispatcher names one of the two implementations per layer."""
+    from paper_2011_06295_amd import workloads as wl
+    work = wl.vgg16(8, "f32")
+    net = _net(work)
+    net.run_chain(wl.make_input(work))
+    rows = net.compare_with_dense(reps=3)
+    assert len(rows) == 13
+    for r, run in zip(rows, net.runs):
+        scale = float(run.y.abs().max())
+        assert r["choice"] in ("sparse", "dense") and r["sparse_us"] > 0 and r["dense_us"] > 0
+        assert r["max_abs_diff"] <= 2e-5 * max(scale, 1.0), r
+    net.close()
+
+
 def test_config5_unify_flag_matches_plain_rows():
     """Ragged rows padded to a unified count with explicit zeros give the same numbers."""
     import torch
