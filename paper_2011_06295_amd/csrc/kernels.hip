@@ -9,9 +9,10 @@
 // (image groups of V element-wise interleaved images stacked vertically, each
 // with `pad` zero rows above and `pad` zero columns to the left; see Plan in
 // internal.h).  A workgroup owns `span` consecutive lattice positions and keeps
-// the rows they touch, for Cc channels at a time, in LDS.  A lane owns one
-// position: tap (r, s) of channel c is the LDS element at
-// position + c*CS + r*Wp + s, so the 64 lanes of a wavefront always read 64
+// what they touch, for Cc channels at a time, in LDS: the lattice rows they
+// span, or, for maps much wider than a tile, R bands of span + S - 1 elements.
+// A lane owns one position: tap (r, s) of channel c is the LDS element at
+// position + c*CS + r*pitch + s, so the 64 lanes of a wavefront always read 64
 // consecutive, naturally aligned V-vectors (one ds_read_b128 for 4 fp32 or
 // 8 fp16 images), free of bank conflicts whatever the tap.  Positions that fall
 // on padding compute a value nobody stores.  A wavefront owns KW output
@@ -19,12 +20,14 @@
 // Stored weights arrive as (weight, LDS offset) pairs, wave-uniform, fetched in
 // batches of kBatch through the scalar path, a batch ahead of their use; per
 // pair a lane does one vector LDS read and V fused multiply-adds in fp32.
+// Channel chunks alternate between two LDS buffers: the global loads of the
+// next chunk are issued into registers during the arithmetic of the current
+// one and written to the other buffer after it (one barrier per chunk).
 #include <hip/hip_runtime.h>
 
 #include "internal.h"
 
 namespace sc {
-
 
 // Read-only plan tables are addressed through the constant address space: a
 // wave-uniform load from it is always issued on the scalar path (s_load), which
@@ -78,9 +81,9 @@ struct Vec<T, 1> {
 };
 
 // Developer instrumentation (builds with -DSC_PHASE_TIMING only): every
-// wavefront accumulates the 100 MHz wall-clock ticks
-// spent in [0] set-up, [1] staging (incl. the wait for all stagers), [2] the
-// gather-FMA, [3] waiting for copies and the other wavefronts, [4] the
+// wavefront accumulates the 100 MHz wall-clock ticks spent in [0] set-up and
+// the first chunk's staging, [1] starting a chunk's loads, [2] the gather-FMA,
+// [3] depositing the next chunk and waiting for the other wavefronts, [4] the
 // store, and reports [5] its start and [6] its end tick (8 counters per
 // wavefront, 16 wavefront slots per workgroup).
 #ifdef SC_PHASE_TIMING
