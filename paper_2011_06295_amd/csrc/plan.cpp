@@ -18,6 +18,7 @@
 #include <algorithm>
 #include <climits>
 #include <cmath>
+#include <vector>
 
 #include "../../include/sparse_conv.h"
 
@@ -260,8 +261,34 @@ int build_plan(const Csr& csr, int C, int R, int S, int elem_bytes, const Geomet
     p.grid = (int)grid;
 
     // ---- tables
+    // Output channel of every accumulator slot (kb, wk, kk).  Rows of equal length (the paper's
+    // unified count) keep their order.  Ragged rows are dealt out longest first, back and forth
+    // over all wavefronts of all channel blocks, so that wavefronts and workgroups get about
+    // the same number of stored weights.
     p.krow.assign((size_t)p.kblocks * KB, -1);
-    for (int k = 0; k < K; ++k) p.krow[k] = k;  // slot (kb, wk, kk) <-> channel kb*KB + wk*KW + kk
+    {
+        int lo = INT_MAX, hi = 0;
+        for (int k = 0; k < K; ++k) {
+            const int n = csr.rowptr[k + 1] - csr.rowptr[k];
+            lo = std::min(lo, n);
+            hi = std::max(hi, n);
+        }
+        if (hi == lo) {
+            for (int k = 0; k < K; ++k) p.krow[k] = k;
+        } else {
+            std::vector<int> order(K);
+            for (int k = 0; k < K; ++k) order[k] = k;
+            std::stable_sort(order.begin(), order.end(), [&](int x, int y) {
+                return csr.rowptr[x + 1] - csr.rowptr[x] > csr.rowptr[y + 1] - csr.rowptr[y];
+            });
+            const int bins = p.kblocks * p.WK;   // wavefronts over all channel blocks
+            for (int i = 0; i < K; ++i) {
+                const int round = i / bins, j = i % bins;
+                const int bin = (round & 1) ? bins - 1 - j : j;
+                p.krow[(size_t)bin * p.KW + round] = order[i];   // slot (bin = kb*WK + wk, kk = round)
+            }
+        }
+    }
 
     const int RS = R * S;
     const int nchunks = p.nchunks;
