@@ -219,8 +219,6 @@ __global__ __launch_bounds__(1024) void tile_kernel(const KernelArgs a)
     // reject element, the slot table
     vec* tile = reinterpret_cast<vec*>(smem);
     const int reject = a.nbuf * a.tile_elems;
-    // padding rows/columns and absent images stay zero for the whole kernel
-    for (int u = tid; u < reject; u += nthreads) tile[u] = VT::zero();
 
     // Staging table.  What a tile holds of one channel is the same for every
     // channel: a set of SL slots, each one real (non-padding) element of the
@@ -424,11 +422,15 @@ __global__ __launch_bounds__(1024) void tile_kernel(const KernelArgs a)
 
     unsigned warm = touch();  // chunk 0's entries
     begin_chunk(0);
-    __syncthreads();  // zero fill and slot table complete
+    __syncthreads();  // slot table complete
     prepare_units();
     fetch_begin(0);
 #pragma unroll
     for (int t = 0; t < kStage; ++t) fetch_unit(t);
+    // while the first loads are in flight: padding rows/columns and absent images are zeroed
+    // once and stay zero for the whole kernel (staging writes real elements only)
+    for (int u = tid; u < reject; u += nthreads) tile[u] = VT::zero();
+    __syncthreads();  // zero fill complete
     deposit(0);
     for (int p = 1; p < a.npass; ++p) {
         fetch_more(p);
