@@ -101,6 +101,9 @@ def main():
     ap.add_argument("--workload", default="vgg16_f32")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--launch", default="", help="comma separated launch override applied to every layer")
+    ap.add_argument("--autotune", type=int, default=0,
+                    help="before the warm-up, let every layer measure this many of its best-ranked launch "
+                         "configurations and keep the fastest (0: the cost estimate's first choice)")
     ap.add_argument("--compare-dense", action="store_true",
                     help="also time the platform's dense convolution (torch / MIOpen) per layer and report which "
                          "of the two a dispatcher would pick")
@@ -125,6 +128,8 @@ def main():
     net.run_chain(wl.make_input(work))
     N = work.N
     b = 2 if work.dtype == "f16" else 4
+    if args.autotune > 0 and not args.launch:
+        net.autotune(args.autotune)
 
     for _ in range(args.warmup):
         net.step()
@@ -207,7 +212,10 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": work.dtype, "data": "synthetic",
         "config": {"workload": f"{work.name}, batch {N}, {nl} sparse conv layer(s), conv only, inputs resident in HBM",
-                   "layers": nl, "batch": N, "total_macs": total_macs},
+                   "layers": nl, "batch": N, "total_macs": total_macs,
+                   "launch": (f"override {args.launch}" if args.launch else
+                              f"measured best of {args.autotune} ranked candidates per layer" if args.autotune > 0
+                              else "cost estimate")},
         "roofline": roofline,
         "layers": layers,
     }

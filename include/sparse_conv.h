@@ -119,6 +119,25 @@ int sparse_conv_get_csr(sparse_conv_t h, int* K, long long* nnz,
 int sparse_conv_set_launch(sparse_conv_t h, const int* params, int nparams);
 
 /*
+ * sparse_conv_autotune - choose the launch configuration of one geometry by
+ * measurement (section 8: the number of thread blocks per layer "was
+ * experimentally fixed for each layer"; section 9 quotes the loss of an untuned
+ * choice).  Runs the layer on the given buffers with the max_candidates
+ * (<= 0: 8) configurations the cost estimate ranks best, within whatever
+ * sparse_conv_set_launch has pinned, times each with events on `stream`, and
+ * keeps the fastest for later forwards of this (N,H,W,stride,pad).
+ *   input, output, N..pad, stream   as for sparse_conv_forward (N > 0); output is
+ *            overwritten with the layer's result.
+ *   best_us  if not NULL receives the kept configuration's time per launch, in us.
+ * Synchronous (it waits for its own measurements) and it allocates plan
+ * buffers: call it once, outside timed or captured regions.
+ * sparse_conv_set_launch discards what was tuned.
+ */
+int sparse_conv_autotune(sparse_conv_t h, const void* input, void* output,
+                         int N, int H, int W, int stride, int pad, void* stream,
+                         int max_candidates, float* best_us);
+
+/*
  * sparse_conv_set_epilogue - what the store step does with a finished sum
  * (section 3: the sum over the filter is added to the bias of its output channel
  * and the activation function is applied).  Default: store the bare sum.

@@ -24,7 +24,7 @@ LIB_PATH = os.environ.get("SPARSECONV_LIBRARY") or os.path.join(
 
 EXPORTS = (
     "sparse_conv_create", "sparse_conv_output_shape", "sparse_conv_forward",
-    "sparse_conv_get_csr", "sparse_conv_set_launch", "sparse_conv_get_launch", "sparse_conv_set_epilogue",
+    "sparse_conv_get_csr", "sparse_conv_set_launch", "sparse_conv_get_launch", "sparse_conv_set_epilogue", "sparse_conv_autotune",
     "sparse_conv_last_hip_error", "sparse_conv_strerror", "sparse_conv_destroy",
 )
 
@@ -55,6 +55,8 @@ def _load():
     lib.sparse_conv_set_launch.argtypes = [vp, ip, C.c_int]
     lib.sparse_conv_get_launch.argtypes = [vp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, ip]
     lib.sparse_conv_set_epilogue.argtypes = [vp, vp, C.c_uint]
+    lib.sparse_conv_autotune.argtypes = [vp, vp, vp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, vp, C.c_int,
+                                         C.POINTER(C.c_float)]
     lib.sparse_conv_last_hip_error.argtypes = [vp]
     lib.sparse_conv_strerror.argtypes = [C.c_int]
     lib.sparse_conv_strerror.restype = C.c_char_p
@@ -136,6 +138,15 @@ def sparse_conv_set_epilogue(handle: int, bias: Optional[np.ndarray], flags: int
     _check(_lib.sparse_conv_set_epilogue(handle, ptr, C.c_uint(flags)), "sparse_conv_set_epilogue", handle)
 
 
+def sparse_conv_autotune(handle: int, input_ptr: int, output_ptr: int, N: int, H: int, W: int, stride: int, pad: int,
+                         stream: int = 0, max_candidates: int = 0) -> float:
+    """Measures the best-ranked launch configurations on the given device buffers; returns the kept one's us per launch."""
+    us = C.c_float(0.0)
+    _check(_lib.sparse_conv_autotune(handle, input_ptr, output_ptr, N, H, W, stride, pad, stream, max_candidates,
+                                     C.byref(us)), "sparse_conv_autotune", handle)
+    return float(us.value)
+
+
 def sparse_conv_get_launch(handle: int, N: int, H: int, W: int, stride: int, pad: int) -> dict:
     arr = (C.c_int * 10)()
     _check(_lib.sparse_conv_get_launch(handle, N, H, W, stride, pad, arr), "sparse_conv_get_launch", handle)
@@ -177,8 +188,7 @@ class SparseConv:
     def get_launch(self, N, H, W, stride=1, pad=0):
         return sparse_conv_get_launch(self.handle, N, H, W, stride, pad)
 
-    def forward(self, x, stride: int = 1, pad: int = 0, out=None):
-        """x: contiguous CUDA tensor [N][C][H][W] of the layer's dtype; returns [N][K][E][F]."""
+    def _buffers(self, x, stride, pad, out):
         import torch
         want = torch.float16 if self.dtype == SC_F16 else torch.float32
         if not x.is_cuda or x.dtype != want or not x.is_contiguous() or x.dim() != 4 or x.shape[1] != self.C:
@@ -189,8 +199,17 @@ class SparseConv:
             out = torch.empty((N, self.K, E, F), dtype=want, device=x.device)
         elif tuple(out.shape) != (N, self.K, E, F) or out.dtype != want or not out.is_contiguous():
             raise ValueError("bad output tensor")
-        stream = torch.cuda.current_stream(x.device).cuda_stream
-        sparse_conv_forward(self.handle, x.data_ptr(), out.data_ptr(), N, H, W, stride, pad, stream)
+        return out, (N, H, W, stride, pad), torch.cuda.current_stream(x.device).cuda_stream
+
+    def autotune(self, x, stride: int = 1, pad: int = 0, out=None, max_candidates: int = 0) -> float:
+        """Picks the launch configuration for x's geometry by measurement (overwrites out); returns its us per launch."""
+        out, geom, stream = self._buffers(x, stride, pad, out)
+        return sparse_conv_autotune(self.handle, x.data_ptr(), out.data_ptr(), *geom, stream, max_candidates)
+
+    def forward(self, x, stride: int = 1, pad: int = 0, out=None):
+        """x: contiguous CUDA tensor [N][C][H][W] of the layer's dtype; returns [N][K][E][F]."""
+        out, geom, stream = self._buffers(x, stride, pad, out)
+        sparse_conv_forward(self.handle, x.data_ptr(), out.data_ptr(), *geom, stream)
         return out
 
     def close(self):

@@ -4,6 +4,8 @@
 #include <algorithm>
 #include <cstring>
 #include <new>
+#include <utility>
+#include <vector>
 
 #include "../../include/sparse_conv.h"
 #include "internal.h"
@@ -41,7 +43,11 @@ int get_plan(sparse_conv_s* h, const Geometry& g, Plan** out)
     if (it == h->plans.end()) {
         std::unique_ptr<Plan> p(new (std::nothrow) Plan());
         if (!p) return SC_ENOMEM;
-        int rc = build_plan(h->csr, h->C, h->R, h->S, h->dtype == SC_F16 ? 2 : 4, g, h->over, *p);
+        const Launch& o = h->over;
+        const bool automatic = !(o.V || o.WP || o.WK || o.KW || o.Cc || o.lds_budget);
+        auto tuned = h->tuned.find(g);
+        const Launch& use = (automatic && tuned != h->tuned.end()) ? tuned->second : h->over;
+        int rc = build_plan(h->csr, h->C, h->R, h->S, h->dtype == SC_F16 ? 2 : 4, g, use, *p);
         if (rc != SC_OK) return rc;
         it = h->plans.emplace(g, std::move(p)).first;
     }
@@ -139,6 +145,7 @@ int sparse_conv_set_launch(sparse_conv_t h, const int* params, int nparams)
     l.V = v[0]; l.WP = v[1]; l.WK = v[2]; l.KW = v[3]; l.Cc = v[4]; l.lds_budget = v[5];
     h->over = l;
     h->plans.clear();
+    h->tuned.clear();
     return SC_OK;
 }
 
@@ -240,6 +247,66 @@ int sparse_conv_forward(sparse_conv_t h, const void* input, void* output,
             h->last_hip = e;
             return SC_EHIP;
         }
+        return SC_OK;
+    } catch (const std::bad_alloc&) {
+        return SC_ENOMEM;
+    } catch (...) {
+        return SC_EHIP;
+    }
+}
+
+int sparse_conv_autotune(sparse_conv_t h, const void* input, void* output,
+                         int N, int H, int W, int stride, int pad, void* stream,
+                         int max_candidates, float* best_us)
+{
+    if (!h || N <= 0 || !input || !output || input == output) return SC_EINVAL;
+    if (!sc::geometry_ok(h, H, W, stride, pad)) return SC_EINVAL;
+    try {
+        const sc::Geometry g{N, H, W, stride, pad};
+        std::vector<std::pair<double, sc::Launch>> ranked;
+        sc::Plan scratch;
+        int rc = sc::build_plan(h->csr, h->C, h->R, h->S, h->dtype == SC_F16 ? 2 : 4, g, h->over, scratch, &ranked);
+        if (rc != SC_OK) return rc;
+        const size_t want = max_candidates > 0 ? (size_t)max_candidates : 8;
+        if (ranked.size() > want) ranked.resize(want);
+        hipStream_t s = static_cast<hipStream_t>(stream);
+        hipEvent_t e0 = nullptr, e1 = nullptr;
+        hipError_t he = hipEventCreate(&e0);
+        if (he == hipSuccess) he = hipEventCreate(&e1);
+        if (he != hipSuccess) {
+            if (e0) (void)hipEventDestroy(e0);
+            h->last_hip = (int)he;
+            return SC_EHIP;
+        }
+        const sc::Launch saved = h->over;
+        sc::Launch best_launch;
+        float best = -1.f;
+        rc = SC_OK;
+        for (const auto& cand : ranked) {
+            h->over = cand.second;
+            h->plans.erase(g);
+            const int warm = 2, reps = 5;
+            for (int i = 0; i < warm && rc == SC_OK; ++i) rc = sparse_conv_forward(h, input, output, N, H, W, stride, pad, stream);
+            if (rc == SC_EUNSUPPORTED) { rc = SC_OK; continue; }   // a candidate this geometry cannot run
+            if (rc != SC_OK) break;
+            he = hipEventRecord(e0, s);
+            for (int i = 0; i < reps && rc == SC_OK; ++i) rc = sparse_conv_forward(h, input, output, N, H, W, stride, pad, stream);
+            if (he == hipSuccess) he = hipEventRecord(e1, s);
+            if (he == hipSuccess) he = hipEventSynchronize(e1);
+            float ms = 0.f;
+            if (he == hipSuccess) he = hipEventElapsedTime(&ms, e0, e1);
+            if (rc != SC_OK) break;
+            if (he != hipSuccess) { h->last_hip = (int)he; rc = SC_EHIP; break; }
+            if (best < 0.f || ms < best) { best = ms; best_launch = cand.second; }
+        }
+        (void)hipEventDestroy(e0);
+        (void)hipEventDestroy(e1);
+        h->over = saved;
+        h->plans.erase(g);
+        if (rc != SC_OK) return rc;
+        if (best < 0.f) return SC_EUNSUPPORTED;
+        h->tuned[g] = best_launch;
+        if (best_us) *best_us = best * 1000.f / 5.f;
         return SC_OK;
     } catch (const std::bad_alloc&) {
         return SC_ENOMEM;

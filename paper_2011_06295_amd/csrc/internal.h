@@ -6,6 +6,7 @@
 #include <map>
 #include <memory>
 #include <tuple>
+#include <utility>
 #include <vector>
 
 namespace sc {
@@ -105,9 +106,10 @@ struct Plan {
 };
 
 // Chooses the configuration (honouring overrides) and builds the host tables.
-// Returns an SC_* status.
+// With `ranked` it only lists the candidate configurations (estimated clocks,
+// full override), cheapest first, and builds nothing.  Returns an SC_* status.
 int build_plan(const Csr& csr, int C, int R, int S, int elem_bytes, const Geometry& g,
-               const Launch& over, Plan& plan);
+               const Launch& over, Plan& plan, std::vector<std::pair<double, Launch>>* ranked = nullptr);
 
 // ---------------------------------------------------------------- kernels
 
@@ -158,6 +160,7 @@ struct sparse_conv_s {
     sc::Launch over;
     float* d_bias = nullptr;   // device copy of the epilogue bias (owned)
     unsigned epilogue = 0;
+    std::map<sc::Geometry, sc::Launch> tuned;   // per geometry: configuration found by sparse_conv_autotune
     std::map<sc::Geometry, std::unique_ptr<sc::Plan>> plans;
     int last_hip = 0;
 };

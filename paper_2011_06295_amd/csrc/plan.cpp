@@ -18,6 +18,7 @@
 #include <algorithm>
 #include <climits>
 #include <cmath>
+#include <utility>
 #include <vector>
 
 #include "../../include/sparse_conv.h"
@@ -122,7 +123,7 @@ FastDiv make_fastdiv(int d)
 }
 
 int build_plan(const Csr& csr, int C, int R, int S, int elem_bytes, const Geometry& g,
-               const Launch& over, Plan& p)
+               const Launch& over, Plan& p, std::vector<std::pair<double, Launch>>* ranked)
 {
     const int K = csr.K;
     const int st = g.stride, pad = g.pad;
@@ -220,6 +221,11 @@ int build_plan(const Csr& csr, int C, int R, int S, int elem_bytes, const Geomet
                             if (!(over.WP || over.WK || over.KW || over.Cc || over.lds_budget)) continue;
                             t = 1e30;   // an explicit request is honoured even where the estimate expects no residency
                         }
+                        if (ranked) {
+                            Launch l;
+                            l.V = V; l.WP = wp; l.WK = wk; l.KW = kw; l.Cc = Cc;
+                            ranked->emplace_back(t, l);
+                        }
                         if (best_t < 0 || t < best_t) {
                             best_t = t;
                             best = c;
@@ -232,6 +238,21 @@ int build_plan(const Csr& csr, int C, int R, int S, int elem_bytes, const Geomet
     }
     if (best_t < 0 && too_many_positions) return SC_EUNSUPPORTED;
     if (best_t < 0) return SC_EUNSUPPORTED;
+    if (ranked) {   // the caller only wants the candidates, cheapest estimate first, each once
+        std::stable_sort(ranked->begin(), ranked->end(),
+                         [](const std::pair<double, Launch>& x, const std::pair<double, Launch>& y) { return x.first < y.first; });
+        std::vector<std::pair<double, Launch>> uniq;
+        for (const auto& e : *ranked) {
+            bool seen = false;
+            for (const auto& u : uniq)
+                seen = seen || (u.second.V == e.second.V && u.second.WP == e.second.WP && u.second.WK == e.second.WK &&
+                                u.second.KW == e.second.KW && u.second.Cc == e.second.Cc);
+            if (!seen) uniq.push_back(e);
+            if (uniq.size() >= 64) break;
+        }
+        ranked->swap(uniq);
+        return SC_OK;
+    }
 
     const Shape& s = bs;
     const int V = best.V;

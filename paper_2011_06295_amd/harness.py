@@ -72,6 +72,11 @@ class Network:
         torch.cuda.synchronize()
         return x
 
+    def autotune(self, max_candidates: int = 0):
+        """Tunes every layer's launch configuration on its resident buffers (after run_chain)."""
+        return [run.layer.autotune(run.x, run.spec.stride, run.spec.pad, out=run.y, max_candidates=max_candidates)
+                for run in self.runs]
+
     def step(self):
         """One pass of the hot path: every layer's convolution on its resident input."""
         for run in self.runs:

@@ -96,6 +96,11 @@ def test_argument_validation_returns_status_codes():
     assert lib.sparse_conv_set_epilogue(None, None, 0) == B.SC_EINVAL
     assert lib.sparse_conv_set_epilogue(h, None, 2) == B.SC_EINVAL                               # unknown epilogue flag
     assert lib.sparse_conv_set_epilogue(h, None, B.SC_EPILOGUE_RELU) == B.SC_OK                  # no bias: nothing to copy, needs no GPU
+    assert lib.sparse_conv_autotune(None, 8, 16, 1, 4, 4, 1, 0, None, 0, None) == B.SC_EINVAL    # arguments are checked before any GPU call
+    assert lib.sparse_conv_autotune(h, None, 16, 1, 4, 4, 1, 0, None, 0, None) == B.SC_EINVAL
+    assert lib.sparse_conv_autotune(h, 8, 8, 1, 4, 4, 1, 0, None, 0, None) == B.SC_EINVAL         # in place
+    assert lib.sparse_conv_autotune(h, 8, 16, 0, 4, 4, 1, 0, None, 0, None) == B.SC_EINVAL        # needs a batch to time
+    assert lib.sparse_conv_autotune(h, 8, 16, 1, 4, 4, 0, 0, None, 0, None) == B.SC_EINVAL        # stride 0
     assert lib.sparse_conv_strerror(B.SC_EINVAL) == b"invalid argument"
     lib.sparse_conv_destroy(h)
     lib.sparse_conv_destroy(None)

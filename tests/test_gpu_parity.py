@@ -167,6 +167,33 @@ def test_bias_and_relu_in_the_store_step(dtype):
     layer.close()
 
 
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+def test_measured_launch_choice_keeps_the_result(dtype):
+    """Section 8 fixes the launch shape per layer by experiment: the measured choice is one of the
+    ranked candidates, later forwards of that geometry use it, and the result does not change."""
+    import torch
+    from paper_2011_06295_amd import binding as B
+    rng = np.random.default_rng(505)
+    N, C, K, R, S, H, W = 9, 24, 40, 3, 3, 14, 14
+    w, m, x = rand_layer(rng, N, C, K, R, S, H, W, density=0.2)
+    ref = oracle_ref(w, m, x, 1, 1, dtype)
+    layer = B.SparseConv(w, m, dtype=dtype)
+    before = run_gpu(layer, x, 1, 1, dtype)
+    xt = torch.from_numpy(x).cuda().to(torch.float16 if dtype == "f16" else torch.float32).contiguous()
+    us = layer.autotune(xt, 1, 1, max_candidates=6)
+    assert us > 0
+    tuned = layer.get_launch(N, H, W, 1, 1)
+    other = layer.get_launch(N + 1, H, W, 1, 1)          # another geometry keeps the estimate's choice
+    assert 64 <= tuned["threads"] <= 1024 and other["threads"] >= 64
+    after = run_gpu(layer, x, 1, 1, dtype)
+    assert_close(after, ref, TOL[dtype], f"autotuned-{dtype}")
+    assert_close(before, ref, TOL[dtype], f"estimated-{dtype}")
+    layer.set_launch([tuned["V"], tuned["WP"], tuned["WK"], tuned["KW"], tuned["Cc"], 0])   # pinning it by hand gives the same plan
+    pinned = layer.get_launch(N, H, W, 1, 1)
+    assert pinned == tuned
+    layer.close()
+
+
 def test_hand_examples_on_gpu():
     import json
     import os
