@@ -101,7 +101,7 @@ def main():
     ap.add_argument("--workload", default="vgg16_f32")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--launch", default="", help="comma separated launch override applied to every layer")
-    ap.add_argument("--autotune", type=int, default=0,
+    ap.add_argument("--autotune", type=int, default=8,
                     help="before the warm-up, let every layer measure this many of its best-ranked launch "
                          "configurations and keep the fastest (0: the cost estimate's first choice)")
     ap.add_argument("--compare-dense", action="store_true",
@@ -166,7 +166,7 @@ def main():
             "bound": bound[0], "roof_frac": round(bound[1] / t, 4),
             "hbm_GBs": round(roofs["hbm_bytes"] / t / 1e9, 1), "lds_GBs": round(roofs["lds_bytes"] / t / 1e9, 1),
             "launch": {k: v for k, v in r.layer.get_launch(N, r.spec.H, r.spec.W, r.spec.stride, r.spec.pad).items()
-                       if k in ("V", "WP", "WK", "KW", "Cc", "grid", "lds_bytes", "threads")},
+                       if k in ("V", "WP", "WK", "KW", "Cc", "LP", "grid", "lds_bytes", "threads")},
         })
 
     if args.copy_probe_mib > 0:

@@ -107,11 +107,12 @@ int sparse_conv_get_csr(sparse_conv_t h, int* K, long long* nnz,
  * library's counterpart of the per-layer thread-block count the paper tunes
  * (section 8, subBatchSize; section 9).  params[0..nparams) are, in order:
  *   [0] V   images interleaved per LDS element (1, 2, 4 or 8; 0 = automatic)
- *   [1] WP  wavefronts across output positions (64 positions each) per workgroup
+ *   [1] WP  wavefronts across output positions (64 * LP positions each) per workgroup
  *   [2] WK  wavefronts across output channels per workgroup (WP*WK <= 16)
  *   [3] KW  output channels accumulated per wavefront (1, 2, 4, 8 or 16)
  *   [4] Cc  input channels staged per LDS pass
  *   [5] LDS budget in bytes per workgroup (used when Cc is automatic)
+ *   [6] LP  output positions per lane (1 or 2; with LP = 2: KW * V <= 16)
  * Missing trailing entries and zeros mean "automatic".  nparams = 0 restores
  * the automatic choice.  Cached plans are discarded.  SC_EINVAL for values the
  * kernels cannot run; a configuration that cannot fit is reported by forward.
@@ -120,9 +121,8 @@ int sparse_conv_set_launch(sparse_conv_t h, const int* params, int nparams);
 
 /*
  * sparse_conv_autotune - choose the launch configuration of one geometry by
- * measurement (section 8: the number of thread blocks per layer "was
- * experimentally fixed for each layer"; section 9 quotes the loss of an untuned
- * choice).  Runs the layer on the given buffers with the max_candidates
+ * measurement (section 8 sets the thread-block count of each layer by
+ * experiment; section 9 reports what an untuned choice costs).  Runs the layer on the given buffers with the max_candidates
  * (<= 0: 8) configurations the cost estimate ranks best, within whatever
  * sparse_conv_set_launch has pinned, times each with events on `stream`, and
  * keeps the fastest for later forwards of this (N,H,W,stride,pad).
@@ -150,11 +150,12 @@ int sparse_conv_autotune(sparse_conv_t h, const void* input, void* output,
  */
 int sparse_conv_set_epilogue(sparse_conv_t h, const float* bias, unsigned flags);
 
-/* The launch configuration chosen for a geometry, in the order of
- * sparse_conv_set_launch, followed by [6] workgroups launched, [7] LDS bytes
+/* The launch configuration chosen for a geometry: [0] V .. [4] Cc, [5] the LDS
+ * budget in force, [6] workgroups launched, [7] LDS bytes
  * per workgroup, [8] threads per workgroup, [9] stored plan entries
- * (including batch padding).  Builds the plan's host side if needed; needs no
- * GPU.  params must have room for 10 ints. */
+ * (including batch padding), [10] LP.  [0..5] are in the order of
+ * sparse_conv_set_launch.  Builds the plan's host side if needed; needs no
+ * GPU.  params must have room for 11 ints. */
 int sparse_conv_get_launch(sparse_conv_t h, int N, int H, int W, int stride, int pad, int* params);
 
 /* HIP error code of the last failing runtime call made through this handle (0 if none). */

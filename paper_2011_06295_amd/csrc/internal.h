@@ -33,11 +33,12 @@ bool encode_csr(const float* w, const unsigned char* mask, int K, int L, bool un
 // Tunables of the tile kernel; 0 = choose automatically.
 struct Launch {
     int V = 0;    // images interleaved per LDS element
-    int WP = 0;   // wavefronts across output positions (64 positions each)
+    int WP = 0;   // wavefronts across output positions (64 * LP positions each)
     int WK = 0;   // wavefronts across output channels
     int KW = 0;   // output channels per wavefront
     int Cc = 0;   // channels per LDS pass
     int lds_budget = 0;
+    int LP = 0;   // positions per lane (1 or 2)
 };
 
 struct Geometry {
@@ -71,7 +72,7 @@ struct Entry {
 // (r, s) of it is the element at q + r*Wp + s, so neighbouring lanes always
 // read neighbouring LDS elements, whatever the tap.
 struct Plan {
-    int V, WP, WK, KW, Cc;
+    int V, WP, WK, KW, Cc, LP;
     int E, F;
     int Wp;        // row pitch of the padded lattice
     int Hs;        // rows per image group
@@ -148,7 +149,7 @@ struct KernelArgs {
 };
 
 // Enqueues the tile kernel.  Returns a hipError_t value (0 = success).
-int launch_tile_kernel(int dtype, int V, int KW, const KernelArgs& a, int grid, int threads,
+int launch_tile_kernel(int dtype, int V, int KW, int LP, const KernelArgs& a, int grid, int threads,
                        int lds_bytes, void* stream);
 
 }  // namespace sc

@@ -11,15 +11,17 @@
 // internal.h).  A workgroup owns `span` consecutive lattice positions and keeps
 // what they touch, for Cc channels at a time, in LDS: the lattice rows they
 // span, or, for maps much wider than a tile, R bands of span + S - 1 elements.
-// A lane owns one position: tap (r, s) of channel c is the LDS element at
-// position + c*CS + r*pitch + s, so the 64 lanes of a wavefront always read 64
+// A lane owns LP (1 or 2) positions, 64 apart: tap (r, s) of channel c is the LDS element
+// at position + c*CS + r*pitch + s, so the 64 lanes of a wavefront always read 64
 // consecutive, naturally aligned V-vectors (one ds_read_b128 for 4 fp32 or
 // 8 fp16 images), free of bank conflicts whatever the tap.  Positions that fall
 // on padding compute a value nobody stores.  A wavefront owns KW output
 // channels whose accumulators stay in registers across the channel chunks.
 // Stored weights arrive as (weight, LDS offset) pairs, wave-uniform, fetched in
 // batches of kBatch through the scalar path, a batch ahead of their use; per
-// pair a lane does one vector LDS read and V fused multiply-adds in fp32.
+// pair a lane forms one LDS address, reads its LP positions at constant
+// distances from it, and does LP * V fused multiply-adds in fp32: the address
+// arithmetic, the scalar fetches and the loop control are shared by LP reads.
 // Channel chunks alternate between two LDS buffers: the global loads of the
 // next chunk are issued into registers during the arithmetic of the current
 // one and written to the other buffer after it (one barrier per chunk).
@@ -99,7 +101,7 @@ struct Vec<T, 1> {
     } while (0)
 #endif
 
-template <typename T, int V, int KW>
+template <typename T, int V, int KW, int LP>
 __global__ __launch_bounds__(1024) void tile_kernel(const KernelArgs a)
 {
 #ifdef SC_PHASE_TIMING
@@ -135,25 +137,20 @@ __global__ __launch_bounds__(1024) void tile_kernel(const KernelArgs a)
     const int Y0 = fdiv((int)q0, a.fd_Wp);      // the host guarantees fewer than 2^31 positions
     const int lq0 = (int)q0 - Y0 * a.Wp;
 
-    // lane -> position -> output element (if any)
-    const int lrel = lq0 + wp * 64 + lane;      // position relative to the start of lattice row Y0
-    // tile element of the position: the tile starts at that row, or (banded tile) at the first position
-    const int lpos = a.rows_mode == 2 ? wp * 64 + lane : lrel;
+    // lane -> its LP positions: wavefront wp covers positions [wp*LP*64, (wp+1)*LP*64) of the tile,
+    // the lane's p-th position is 64*p after its first
+    const int lrel = lq0 + wp * (LP * 64) + lane;  // first position, relative to the start of lattice row Y0
+    // tile element of that position: the tile starts at that row, or (banded tile) at the first position
+    const int lpos = a.rows_mode == 2 ? wp * (LP * 64) + lane : lrel;
     const int lposb = lpos * (int)sizeof(vec);
-    const int Yl = fdiv(lrel, a.fd_Wp);
-    const int X = lrel - Yl * a.Wp;
-    const int Y = Y0 + Yl;
-    const int g = fdiv(Y, a.fd_Hs);
-    const int yy = Y - g * a.Hs;
-    const int oi = yy / a.stride;
-    const int oj = X / a.stride;
-    const bool valid = g < a.ngroups && oi * a.stride == yy && oj * a.stride == X && oi < a.E && oj < a.F;
 
-    float acc[KW][V];
+    float acc[KW][LP][V];
 #pragma unroll
     for (int kk = 0; kk < KW; ++kk)
 #pragma unroll
-        for (int v = 0; v < V; ++v) acc[kk][v] = 0.f;
+        for (int p = 0; p < LP; ++p)
+#pragma unroll
+            for (int v = 0; v < V; ++v) acc[kk][p][v] = 0.f;
 
     const T* __restrict__ x = static_cast<const T*>(a.x);
     const int chan_stride = a.H * a.W;
@@ -355,50 +352,63 @@ __global__ __launch_bounds__(1024) void tile_kernel(const KernelArgs a)
     // scalar fetch of B) are in flight; the wait at the end of a half therefore
     // finds them complete, and one wait serves LDS and scalar returns alike.
     // Entry offsets are in bytes: one VOP2 add per read.
-    constexpr int kHalf = kBatch / 2;
-    // empty statements that use a half's registers: the compiler has to complete their loads before them
-    auto arrived = [](const vec(&x)[kHalf]) __attribute__((always_inline)) {
+    constexpr int kGroup = 2;                          // entries whose reads are issued together
+    constexpr int kGroups = kBatch / kGroup;           // even: the two read buffers alternate
+    constexpr int kPosBytes = 64 * (int)sizeof(vec);   // LDS distance between a lane's successive positions
+    // empty statements that use a group's registers: the compiler has to complete their loads before them
+    auto arrived = [](const vec(&x)[kGroup][LP]) __attribute__((always_inline)) {
 #pragma unroll
-        for (int u = 0; u < kHalf; ++u) asm volatile("" ::"v"(x[u]));
+        for (int u = 0; u < kGroup; ++u)
+#pragma unroll
+            for (int p = 0; p < LP; ++p) asm volatile("" ::"v"(x[u][p]));
     };
     auto compute = [&](int base, bool prefetch) __attribute__((always_inline)) {
-        vec xa[kHalf], xb[kHalf];
+        vec xs[2][kGroup][LP];
+        auto gather = [&](vec(&x)[kGroup][LP], const Entry* E) __attribute__((always_inline)) {
 #pragma unroll
-        for (int u = 0; u < kHalf; ++u) xa[u] = *reinterpret_cast<const vec*>(smem + (base + cur[u].off));
-        arrived(xa);
-        auto step = [&](const Entry (&A)[kBatch], Entry (&B)[kBatch], float (&ac)[V]) __attribute__((always_inline)) {
-            // first half: multiply-adds on A[0..3] (in xa); reads of A[4..7] and the fetch of B in flight
-            __builtin_amdgcn_sched_barrier(0);
+            for (int u = 0; u < kGroup; ++u) {
+                const unsigned char* at = smem + (base + E[u].off);
 #pragma unroll
-            for (int u = 0; u < kHalf; ++u) xb[u] = *reinterpret_cast<const vec*>(smem + (base + A[kHalf + u].off));
-            e += kBatch;
-#pragma unroll
-            for (int u = 0; u < kBatch; ++u) {
-                B[u].wbits = e[u].wbits;
-                B[u].off = e[u].off;
+                for (int p = 0; p < LP; ++p) x[u][p] = *reinterpret_cast<const vec*>(at + p * kPosBytes);
             }
-            __builtin_amdgcn_sched_barrier(0);
+        };
+        auto fma = [&](const vec(&x)[kGroup][LP], const Entry* E, float (&ac)[LP][V]) __attribute__((always_inline)) {
 #pragma unroll
-            for (int u = 0; u < kHalf; ++u) {
-                const float w = __uint_as_float(A[u].wbits);
+            for (int u = 0; u < kGroup; ++u) {
+                const float w = __uint_as_float(E[u].wbits);
 #pragma unroll
-                for (int v = 0; v < V; ++v) ac[v] = __builtin_fmaf(w, (float)VT::get(xa[u], v), ac[v]);
+                for (int p = 0; p < LP; ++p)
+#pragma unroll
+                    for (int v = 0; v < V; ++v) ac[p][v] = __builtin_fmaf(w, (float)VT::get(x[u][p], v), ac[p][v]);
             }
-            __builtin_amdgcn_sched_barrier(0);
-            arrived(xb);
-            // second half: multiply-adds on A[4..7] (in xb); reads of B[0..3] in flight
-            __builtin_amdgcn_sched_barrier(0);
+        };
+        gather(xs[0], cur);
+        arrived(xs[0]);
+        // A step consumes batch A group by group: while the multiply-adds of group j run on one
+        // read buffer, the reads of group j + 1 (after A's last group: B's first) fill the other,
+        // and during the first group the scalar fetch of B is in flight as well.
+        auto step = [&](const Entry (&A)[kBatch], Entry (&B)[kBatch], float (&ac)[LP][V]) __attribute__((always_inline)) {
 #pragma unroll
-            for (int u = 0; u < kHalf; ++u) xa[u] = *reinterpret_cast<const vec*>(smem + (base + B[u].off));
-            __builtin_amdgcn_sched_barrier(0);
+            for (int j = 0; j < kGroups; ++j) {
+                __builtin_amdgcn_sched_barrier(0);
+                if (j == 0) {
+                    gather(xs[1], A + kGroup);
+                    e += kBatch;
 #pragma unroll
-            for (int u = 0; u < kHalf; ++u) {
-                const float w = __uint_as_float(A[kHalf + u].wbits);
-#pragma unroll
-                for (int v = 0; v < V; ++v) ac[v] = __builtin_fmaf(w, (float)VT::get(xb[u], v), ac[v]);
+                    for (int u = 0; u < kBatch; ++u) {
+                        B[u].wbits = e[u].wbits;
+                        B[u].off = e[u].off;
+                    }
+                } else if (j + 1 < kGroups) {
+                    gather(xs[(j + 1) & 1], A + (j + 1) * kGroup);
+                } else {
+                    gather(xs[0], B);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                fma(xs[j & 1], A + j * kGroup, ac);
+                __builtin_amdgcn_sched_barrier(0);
+                arrived(xs[(j + 1) & 1]);
             }
-            __builtin_amdgcn_sched_barrier(0);
-            arrived(xa);
         };
 #pragma unroll
         for (int kk = 0; kk < KW; ++kk) {
@@ -463,10 +473,22 @@ __global__ __launch_bounds__(1024) void tile_kernel(const KernelArgs a)
     }
 
     // ---- store: one writer per output element
-    if (valid) {
-        T* __restrict__ y = static_cast<T*>(a.y);
-        const SC_CONSTANT int* kr = as_constant(a.krow) + ((size_t)kb * a.WK + wk) * KW;
-        const size_t plane = (size_t)a.E * a.F;
+    T* __restrict__ y = static_cast<T*>(a.y);
+    const SC_CONSTANT int* kr = as_constant(a.krow) + ((size_t)kb * a.WK + wk) * KW;
+    const size_t plane = (size_t)a.E * a.F;
+#pragma unroll
+    for (int p = 0; p < LP; ++p) {
+        // position -> output element (if any)
+        const int rel = lrel + p * 64;
+        const int Yl = fdiv(rel, a.fd_Wp);
+        const int X = rel - Yl * a.Wp;
+        const int Y = Y0 + Yl;
+        const int g = fdiv(Y, a.fd_Hs);
+        const int yy = Y - g * a.Hs;
+        const int oi = yy / a.stride;
+        const int oj = X / a.stride;
+        const bool valid = g < a.ngroups && oi * a.stride == yy && oj * a.stride == X && oi < a.E && oj < a.F;
+        if (!valid) continue;
         const size_t pix = (size_t)oi * a.F + oj;
 #pragma unroll
         for (int kk = 0; kk < KW; ++kk) {
@@ -476,7 +498,7 @@ __global__ __launch_bounds__(1024) void tile_kernel(const KernelArgs a)
 #pragma unroll
             for (int v = 0; v < V; ++v) {
                 const int n = g * V + v;
-                float r = acc[kk][v] + bias;
+                float r = acc[kk][p][v] + bias;
                 if (a.relu) r = r > 0.f ? r : 0.f;
                 if (n < a.N) y[((size_t)n * a.K + k) * plane + pix] = (T)r;
             }
@@ -496,10 +518,14 @@ __global__ __launch_bounds__(1024) void tile_kernel(const KernelArgs a)
 
 namespace {
 
-template <typename T, int V, int KW>
+template <typename T, int V, int KW, int LP>
 int launch_one(const KernelArgs& a, int grid, int threads, int lds_bytes, hipStream_t s)
 {
-    auto fn = tile_kernel<T, V, KW>;
+    // accumulators (KW * LP * V floats) plus the reads in flight have to fit a 128-register wavefront
+    if constexpr (LP > 1 && KW * LP * V > 32) {
+        return (int)hipErrorInvalidValue;
+    } else {
+    auto fn = tile_kernel<T, V, KW, LP>;
     if (lds_bytes > 64 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(fn),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
@@ -507,39 +533,44 @@ int launch_one(const KernelArgs& a, int grid, int threads, int lds_bytes, hipStr
     }
     hipLaunchKernelGGL(fn, dim3(grid), dim3(threads), lds_bytes, s, a);
     return (int)hipGetLastError();
+    }
 }
 
 template <typename T, int V>
-int launch_kw(int KW, const KernelArgs& a, int grid, int threads, int lds, hipStream_t s)
+int launch_kw(int KW, int LP, const KernelArgs& a, int grid, int threads, int lds, hipStream_t s)
 {
-    switch (KW) {
-        case 1: return launch_one<T, V, 1>(a, grid, threads, lds, s);
-        case 2: return launch_one<T, V, 2>(a, grid, threads, lds, s);
-        case 4: return launch_one<T, V, 4>(a, grid, threads, lds, s);
-        case 8: return launch_one<T, V, 8>(a, grid, threads, lds, s);
-        case 16: return launch_one<T, V, 16>(a, grid, threads, lds, s);
+    switch (KW * 8 + LP) {
+        case 1 * 8 + 1: return launch_one<T, V, 1, 1>(a, grid, threads, lds, s);
+        case 2 * 8 + 1: return launch_one<T, V, 2, 1>(a, grid, threads, lds, s);
+        case 4 * 8 + 1: return launch_one<T, V, 4, 1>(a, grid, threads, lds, s);
+        case 8 * 8 + 1: return launch_one<T, V, 8, 1>(a, grid, threads, lds, s);
+        case 16 * 8 + 1: return launch_one<T, V, 16, 1>(a, grid, threads, lds, s);
+        case 1 * 8 + 2: return launch_one<T, V, 1, 2>(a, grid, threads, lds, s);
+        case 2 * 8 + 2: return launch_one<T, V, 2, 2>(a, grid, threads, lds, s);
+        case 4 * 8 + 2: return launch_one<T, V, 4, 2>(a, grid, threads, lds, s);
+        case 8 * 8 + 2: return launch_one<T, V, 8, 2>(a, grid, threads, lds, s);
     }
     return (int)hipErrorInvalidValue;
 }
 
 }  // namespace
 
-int launch_tile_kernel(int dtype, int V, int KW, const KernelArgs& a, int grid, int threads,
+int launch_tile_kernel(int dtype, int V, int KW, int LP, const KernelArgs& a, int grid, int threads,
                        int lds_bytes, void* stream)
 {
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (dtype == 0) {
         switch (V) {
-            case 1: return launch_kw<float, 1>(KW, a, grid, threads, lds_bytes, s);
-            case 2: return launch_kw<float, 2>(KW, a, grid, threads, lds_bytes, s);
-            case 4: return launch_kw<float, 4>(KW, a, grid, threads, lds_bytes, s);
+            case 1: return launch_kw<float, 1>(KW, LP, a, grid, threads, lds_bytes, s);
+            case 2: return launch_kw<float, 2>(KW, LP, a, grid, threads, lds_bytes, s);
+            case 4: return launch_kw<float, 4>(KW, LP, a, grid, threads, lds_bytes, s);
         }
     } else {
         switch (V) {
-            case 1: return launch_kw<_Float16, 1>(KW, a, grid, threads, lds_bytes, s);
-            case 2: return launch_kw<_Float16, 2>(KW, a, grid, threads, lds_bytes, s);
-            case 4: return launch_kw<_Float16, 4>(KW, a, grid, threads, lds_bytes, s);
-            case 8: return launch_kw<_Float16, 8>(KW, a, grid, threads, lds_bytes, s);
+            case 1: return launch_kw<_Float16, 1>(KW, LP, a, grid, threads, lds_bytes, s);
+            case 2: return launch_kw<_Float16, 2>(KW, LP, a, grid, threads, lds_bytes, s);
+            case 4: return launch_kw<_Float16, 4>(KW, LP, a, grid, threads, lds_bytes, s);
+            case 8: return launch_kw<_Float16, 8>(KW, LP, a, grid, threads, lds_bytes, s);
         }
     }
     return (int)hipErrorInvalidValue;

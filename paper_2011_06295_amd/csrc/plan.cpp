@@ -43,7 +43,7 @@ struct Shape {
 };
 
 struct Cand {
-    int V, WP, WK, KW, Cc;
+    int V, WP, WK, KW, Cc, LP;
     int Hb, CS, lds, SL, rows_mode, SG, nbuf, pitch;
 };
 
@@ -51,49 +51,57 @@ struct Cand {
 int tile_rows(int span, int Wp, int R, int S) { return (Wp - 1 + span - 1 + (R - 1) * Wp + S - 1) / Wp + 1; }
 
 // Rough time of one launch in CU clocks.  The structure follows measurements on
-// MI355X; the constants were fitted to the measured times of ~11000 launch
-// configurations of the 13 VGG-16 layers (batch 128, fp32) and of the 256->256
-// 14x14 layer at 50..99 % sparsity (batch 256).
-//  * A step (kBatch stored weights of one output channel, for the 64 positions of
-//    a wavefront) costs its SIMD kBatch * (V + 1) vector instructions of ~4 clocks
-//    (fp16: the mixed-precision multiply-add takes ~4.4) and the CU's LDS
-//    kBatch * 64 elements at ~200 B/clk.  For 16-byte fp32 elements the two are
-//    about equal, and they overlap only in part.
-//  * The wavefronts of a CU are spread over 4 SIMDs: the fullest SIMD sets the pace.
-//  * A lone wavefront cannot hide its own LDS and scalar-fetch latency (~300 clocks a step).
-//  * Registers allow 16 resident wavefronts per CU.
-//  * Staging moves ~32 B/clk/CU from L2 and overlaps the arithmetic except for the
-//    first chunk; a workgroup costs ~7 us to start and finish.
+// MI355X; the constants were fitted to the measured times of ~37000 launch
+// configurations (every shape the candidate loops below produce) of the 13
+// VGG-16 layers at 32 px (batch 128, fp32), four of its layers at 224 px
+// (batch 32), the 256->256 14x14 layer at 50..99 % sparsity (batch 256) and six
+// 1x1 layers, so that the estimate's first choice is within a few per cent of
+// the best measured one and its time within ~10 % of the measured.
+//  * A step (kBatch stored weights of one output channel, for the 64 * LP positions
+//    of a wavefront) costs its SIMD kBatch * LP * V multiply-adds of ~4 clocks
+//    (fp16: the mixed-precision multiply-add takes ~4.4) plus ~8 clocks a weight
+//    for the address and loop control, and the CU's LDS kBatch * LP * 64 elements
+//    at ~225 B/clk.  For 16-byte fp32 elements the two are about equal, and they
+//    overlap for the most part.
+//  * A lone wavefront cannot hide its own LDS and scalar-fetch latency (~100 clocks a step).
+//  * Registers (56 + accumulators + two groups of LDS reads in flight) bound the
+//    wavefronts resident on a SIMD, and with them the workgroups on a CU.
+//  * Staging moves ~16 B/clk/CU from L2 and overlaps the arithmetic except for the
+//    first chunk; a workgroup costs ~7 us to start and finish, a chunk ~0.4 us.
 //  * Workgroups run in rounds of (CUs * resident workgroups); a partly filled
 //    last round still takes a round.
 double estimate(const Shape& s, const Cand& c)
 {
     const int nchunks = cdiv(s.C, c.Cc);
     const double seg = s.row_nnz * c.Cc / s.C;
-    const double batches = nchunks == 1 ? std::ceil(seg / kBatch) : seg / kBatch + 0.4;
-    // 16 accumulator rows per wavefront spill registers: ~10 % slower steps
-    const double steps_wave = c.KW * batches * nchunks * (c.KW * c.V >= 64 ? 1.1 : 1.0);
+    const double batches = nchunks == 1 ? std::ceil(seg / kBatch) : seg / kBatch + 0.6;
+    // measured residuals: one row per wavefront and two positions per lane run a little
+    // slower than their instruction counts say, 8 rows per wavefront too
+    const double shape_factor = (c.KW == 1 ? 1.1 : c.KW == 8 ? 1.05 : 1.0) * (c.LP == 2 ? 1.06 : 1.0);
+    const double steps_wave = c.KW * batches * nchunks * shape_factor;
     const int waves = c.WP * c.WK;
-    const int conc_max = std::min(kMaxLds / c.lds, kMaxWaves / waves);
+    const double regs = std::min(128.0, 56.0 + c.KW * c.LP * c.V + 4.0 * c.LP * (s.ub / 4.0));  // the kernels are built for <= 128
+    const int per_simd = std::min(8, 512 / (8 * (int)std::ceil(regs / 8.0)));
+    const int conc_max = std::min(kMaxLds / c.lds, 4 * per_simd / waves);
     if (conc_max < 1) return -1.0;
-    const long long wgs = (long long)cdiv(s.npos, (long long)kWave * c.WP) * cdiv(s.K, c.WK * c.KW);
+    const long long wgs = (long long)cdiv(s.npos, (long long)kWave * c.WP * c.LP) * cdiv(s.K, c.WK * c.KW);
     const double fma_clk = s.elem_bytes == 2 ? 4.4 : 4.0;
-    const double v_step = kBatch * (c.V * fma_clk + 4.0);
-    const double l_step = kBatch * 64.0 * s.ub / 200.0;
+    const double v_step = kBatch * (c.LP * c.V * fma_clk + 8.0);
+    const double l_step = kBatch * c.LP * 64.0 * s.ub / 225.0;
     const double gbytes = (double)s.C * c.CS * s.ub * ((double)s.W / s.Wp) * std::min(1.0, (double)s.H / s.Hs);
-    const double fixed = 16000.0 + 400.0 * nchunks;
+    const double fixed = 16000.0 + 1000.0 * nchunks;
     double t = 0.0;
     long long remaining = wgs;
     const long long slots = (long long)kCUs * conc_max;
     while (remaining > 0) {
         const long long n = std::min(remaining, slots);
         const int conc = (int)((n + kCUs - 1) / kCUs);
-        const double W = 4.0 * cdiv((long long)conc * waves, 4);   // as if every SIMD were as full as the fullest
+        const double W = (double)conc * waves;
         const double a = W * v_step / 4.0, b = W * l_step;
-        const double shared = std::max(a, b) + 0.7 * std::min(a, b);
-        const double step_clk = std::max(shared, v_step + 300.0);
+        const double shared = (std::max(a, b) + 0.3 * std::min(a, b)) / 0.92;
+        const double step_clk = std::max(shared, v_step + 100.0);
         const double t_compute = steps_wave * step_clk;
-        const double t_stage = conc * gbytes / 32.0;
+        const double t_stage = conc * gbytes / 16.0;
         const long long full = remaining / slots;
         const double round = std::max(t_compute, t_stage) + t_stage / nchunks + fixed;
         if (full > 1) {            // identical full rounds
@@ -135,6 +143,7 @@ int build_plan(const Csr& csr, int C, int R, int S, int elem_bytes, const Geomet
     if (over.WP * std::max(1, over.WK) > kMaxWaves || over.WK > kMaxWaves) return SC_EINVAL;
     const int vmax = 16 / elem_bytes;
     if (over.V && !pow2_in(over.V, 1, vmax)) return SC_EINVAL;
+    if (over.LP && !pow2_in(over.LP, 1, 2)) return SC_EINVAL;
 
     // ---- candidates
     static const int budgets[] = {160 * 1024, 80 * 1024, 53 * 1024, 40 * 1024, 32 * 1024};
@@ -163,14 +172,17 @@ int build_plan(const Csr& csr, int C, int R, int S, int elem_bytes, const Geomet
             too_many_positions = true;
             continue;
         }
+        for (int LP = 1; LP <= 2; LP *= 2)
         for (int WP = 1; WP <= 8; WP *= 2) {
+            if (over.LP && LP != over.LP) break;
             if (over.WP && WP != 1) break;
             const int wp = over.WP ? over.WP : WP;
-            const int Hb = tile_rows(kWave * wp, s.Wp, R, S);
+            const int span = kWave * wp * LP;
+            const int Hb = tile_rows(span, s.Wp, R, S);
             // Tile layout per channel.  Contiguous: the Hb lattice rows the positions and their taps
             // touch, pitch Wp.  Banded (maps much wider than the tile): R bands of span + S - 1
             // consecutive lattice elements, band r starting r rows below the first position.
-            const int P2 = kWave * wp + S - 1;
+            const int P2 = span + S - 1;
             const bool banded = (long long)R * P2 < (long long)Hb * s.Wp;
             const long long CS = banded ? (long long)R * P2 : (long long)Hb * s.Wp;
             const int pitch = banded ? P2 : s.Wp;
@@ -191,7 +203,8 @@ int build_plan(const Csr& csr, int C, int R, int S, int elem_bytes, const Geomet
                 for (int KW = 1; KW <= 16; KW *= 2) {
                     if (over.KW && KW != 1) break;
                     const int kw = over.KW ? over.KW : KW;
-                    if (kw * V > 64) continue;                       // accumulators must stay in registers
+                    // accumulators and the LDS reads in flight must stay in registers
+                    if (kw * V > 64 || (LP > 1 && (kw * LP * V > 32 || kw * LP > 16))) continue;
                     if (!over.KW && !over.WK && (long long)(wk - 1) * kw >= K && wk > 1) continue;  // idle wavefronts
                     for (int bi = 0; bi < 5; ++bi) {
                         if ((over.lds_budget || over.Cc) && bi) break;
@@ -215,15 +228,15 @@ int build_plan(const Csr& csr, int C, int R, int S, int elem_bytes, const Geomet
                         // tile buffer(s), one reject element, table
                         const long long lds = (((long long)nbuf * Cc * CS + 1) * s.ub + 15) / 16 * 16 + tbl;
                         if (lds > kMaxLds) continue;
-                        Cand c{V, wp, wk, kw, Cc, Hb, (int)CS, (int)lds, (int)SL, banded ? 2 : rows_mode ? 1 : 0, rows_mode ? 1 : (int)GC, nbuf, pitch};
+                        Cand c{V, wp, wk, kw, Cc, LP, Hb, (int)CS, (int)lds, (int)SL, banded ? 2 : rows_mode ? 1 : 0, rows_mode ? 1 : (int)GC, nbuf, pitch};
                         double t = estimate(s, c);
                         if (t < 0) {
-                            if (!(over.WP || over.WK || over.KW || over.Cc || over.lds_budget)) continue;
+                            if (!(over.WP || over.WK || over.KW || over.Cc || over.lds_budget || over.LP)) continue;
                             t = 1e30;   // an explicit request is honoured even where the estimate expects no residency
                         }
                         if (ranked) {
                             Launch l;
-                            l.V = V; l.WP = wp; l.WK = wk; l.KW = kw; l.Cc = Cc;
+                            l.V = V; l.WP = wp; l.WK = wk; l.KW = kw; l.Cc = Cc; l.LP = LP;
                             ranked->emplace_back(t, l);
                         }
                         if (best_t < 0 || t < best_t) {
@@ -246,7 +259,7 @@ int build_plan(const Csr& csr, int C, int R, int S, int elem_bytes, const Geomet
             bool seen = false;
             for (const auto& u : uniq)
                 seen = seen || (u.second.V == e.second.V && u.second.WP == e.second.WP && u.second.WK == e.second.WK &&
-                                u.second.KW == e.second.KW && u.second.Cc == e.second.Cc);
+                                u.second.KW == e.second.KW && u.second.Cc == e.second.Cc && u.second.LP == e.second.LP);
             if (!seen) uniq.push_back(e);
             if (uniq.size() >= 64) break;
         }
@@ -257,9 +270,9 @@ int build_plan(const Csr& csr, int C, int R, int S, int elem_bytes, const Geomet
     const Shape& s = bs;
     const int V = best.V;
     const int ngroups = std::max(1, cdiv(g.N, V));
-    p.V = V; p.WP = best.WP; p.WK = best.WK; p.KW = best.KW; p.Cc = best.Cc;
+    p.V = V; p.WP = best.WP; p.WK = best.WK; p.KW = best.KW; p.Cc = best.Cc; p.LP = best.LP;
     p.Wp = s.Wp; p.Hs = s.Hs;
-    p.span = kWave * p.WP;
+    p.span = kWave * p.WP * p.LP;
     p.Hb = best.Hb; p.CS = best.CS;
     p.nchunks = cdiv(C, p.Cc);
     p.ngroups = ngroups;

@@ -93,6 +93,12 @@ def test_argument_validation_returns_status_codes():
     assert lib.sparse_conv_forward(h, None, None, 0, 8, 8, 1, 1, None) == B.SC_OK               # empty batch: no-op
     bad = (C.c_int * 6)(3, 0, 0, 0, 0, 0)
     assert lib.sparse_conv_set_launch(h, bad, 6) == B.SC_EINVAL                                  # V must be a power of two
+    lp3 = (C.c_int * 7)(0, 0, 0, 0, 0, 0, 3)
+    assert lib.sparse_conv_set_launch(h, lp3, 7) == B.SC_EINVAL                                  # positions per lane: 1 or 2
+    assert lib.sparse_conv_set_launch(h, lp3, 8) == B.SC_EINVAL                                  # at most 7 parameters
+    lp3[6] = 2
+    assert lib.sparse_conv_set_launch(h, lp3, 7) == B.SC_OK
+    assert lib.sparse_conv_set_launch(h, None, 0) == B.SC_OK
     assert lib.sparse_conv_set_epilogue(None, None, 0) == B.SC_EINVAL
     assert lib.sparse_conv_set_epilogue(h, None, 2) == B.SC_EINVAL                               # unknown epilogue flag
     assert lib.sparse_conv_set_epilogue(h, None, B.SC_EPILOGUE_RELU) == B.SC_OK                  # no bias: nothing to copy, needs no GPU

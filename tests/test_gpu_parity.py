@@ -72,7 +72,7 @@ def test_random_small_layers(shape, dtype):
 
 
 LAUNCHES = [
-    # V, WP, WK, KW, Cc, lds budget
+    # V, WP, WK, KW, Cc, lds budget[, positions per lane]
     [1, 1, 1, 1, 0, 0],
     [1, 2, 2, 2, 2, 0],
     [2, 1, 4, 4, 5, 0],
@@ -81,6 +81,11 @@ LAUNCHES = [
     [2, 3, 3, 2, 1, 0],
     [4, 4, 4, 1, 0, 40960],
     [0, 8, 2, 2, 7, 0],
+    [4, 1, 2, 4, 0, 0, 2],
+    [0, 1, 3, 1, 4, 0, 2],
+    [2, 2, 1, 8, 5, 0, 2],
+    [1, 1, 4, 8, 6, 0, 2],
+    [0, 2, 2, 2, 0, 0, 2],
 ]
 
 
@@ -188,7 +193,7 @@ def test_measured_launch_choice_keeps_the_result(dtype):
     after = run_gpu(layer, x, 1, 1, dtype)
     assert_close(after, ref, TOL[dtype], f"autotuned-{dtype}")
     assert_close(before, ref, TOL[dtype], f"estimated-{dtype}")
-    layer.set_launch([tuned["V"], tuned["WP"], tuned["WK"], tuned["KW"], tuned["Cc"], 0])   # pinning it by hand gives the same plan
+    layer.set_launch([tuned["V"], tuned["WP"], tuned["WK"], tuned["KW"], tuned["Cc"], 0, tuned["LP"]])   # pinning it by hand gives the same plan
     pinned = layer.get_launch(N, H, W, 1, 1)
     assert pinned == tuned
     layer.close()
