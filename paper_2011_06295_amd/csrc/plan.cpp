@@ -54,7 +54,7 @@ int tile_rows(int span, int Wp, int R, int S) { return (Wp - 1 + span - 1 + (R -
 // MI355X; the constants were fitted to the measured times of ~37000 launch
 // configurations (every shape the candidate loops below produce) of the 13
 // VGG-16 layers at 32 px (batch 128, fp32), four of its layers at 224 px
-// (batch 32), the 256->256 14x14 layer at 50..99 % sparsity (batch 256) and six
+// (batch 128), the 256->256 14x14 layer at 50..99 % sparsity (batch 256) and six
 // 1x1 layers, so that the estimate's first choice is within a few per cent of
 // the best measured one and its time within ~10 % of the measured.
 //  * A step (kBatch stored weights of one output channel, for the 64 * LP positions
