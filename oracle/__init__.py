@@ -38,6 +38,7 @@ def lib():
         _lib.oracle_f16_to_f32.restype = C.c_float
         _lib.oracle_f16_to_f32.argtypes = [C.c_uint16]
         _lib.oracle_csr_rowptr.restype = C.c_longlong
+        _lib.oracle_codebook_csr.restype = C.c_longlong
         _lib.oracle_unify_mask.restype = C.c_int
         _lib.oracle_output_dim.restype = C.c_int
         _lib.oracle_output_dim.argtypes = [C.c_int] * 4
@@ -94,6 +95,31 @@ def csr_encode(w, mask) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
     values = np.empty(nnz, dtype=np.float32)
     lib().oracle_csr_fill(_p(w), _p(m), K, L, _p(colidx), _p(values))
     return rowptr, colidx, values
+
+
+def codebook_csr_encode(index, centroids, mask):
+    """CSR of cluster-quantised weights: (rowptr, colidx, packed 4-bit codes uint8 [ceil(nnz/2)],
+    centroid binary16 bits uint16 [16], values float32 [nnz] = centroid of each stored entry).
+    mask may hold 0/1/2 (2: explicit zero of the unify step)."""
+    idx = np.ascontiguousarray(index, dtype=np.uint8)
+    cen = _f32(centroids)
+    m = np.ascontiguousarray(mask, dtype=np.uint8)
+    assert cen.size == 16 and m.size == idx.size
+    K = idx.shape[0]
+    L = idx.size // K
+    rowptr = np.empty(K + 1, dtype=np.int32)
+    nnz = lib().oracle_csr_rowptr(_p(m), K, L, _p(rowptr))
+    colidx = np.empty(nnz, dtype=np.int32)
+    unused = np.empty(nnz, dtype=np.float32)
+    lib().oracle_csr_fill(_p(np.zeros(idx.size, dtype=np.float32)), _p(m), K, L, _p(colidx), _p(unused))
+    bits = np.empty(16, dtype=np.uint16)
+    packed = np.zeros((nnz + 1) // 2, dtype=np.uint8)
+    values = np.empty(nnz, dtype=np.float32)
+    got = lib().oracle_codebook_csr(_p(idx), _p(cen), _p(m), K, L, _p(bits), _p(packed), _p(values))
+    if got < 0:
+        raise ValueError("index above 15" if got == -1 else "an explicit zero needs a zero centroid")
+    assert got == nnz
+    return rowptr, colidx, packed, bits, values
 
 
 def sparse_conv(csr, x, K: int, R: int, S: int, stride: int, pad: int,

@@ -10,6 +10,9 @@
  *   - section 3, eq. 1: the convolution (cross-correlation, no kernel flip)
  *     and the output size E = (H + 2*padding - R)/stride + 1 (floor division);
  *   - section 5, eq. 4: pruned weights are w * mask;
+ *   - section 6 (cluster quantisation) and section 9 (its 4-bit configuration):
+ *     every weight is replaced by one of 16 centroids, each held in 16 bits,
+ *     and stored as the 4-bit number of its centroid;
  *   - section 7: CSR of the pruned weights, one row per output channel, three
  *     arrays (values, column index, row pointer), and the option of padding
  *     every row to one unified non-zero count with explicit zeros placed at
@@ -152,6 +155,48 @@ void oracle_csr_fill(const float* w, const unsigned char* mask, int K, int L,
             else memcpy(&values[t], &w[(size_t)k * L + j], 4);
             ++t;
         }
+}
+
+/* Cluster-quantised weights (section 6; section 9: 16 centroids of 16 bits each,
+ * a 4-bit code per weight).  index is [K][L] with values 0..15, centroids[16]
+ * are rounded to binary16 (centroid_bits), mask is 0/1/2 as for oracle_csr_fill.
+ * In CSR order (as oracle_csr_fill) entry t gets code[t] = index of its weight
+ * (mask 1) or the number of the first centroid that is zero (mask 2, an explicit
+ * zero of the unify step); values[t] is that centroid widened to float.  Codes
+ * are packed two to a byte, entry 2i in the low nibble of packed[i], entry 2i+1
+ * in the high nibble, an unused last nibble zero.  Where the paper is silent
+ * this is the reading: centroid numbers are taken as given (clustering itself
+ * belongs to model preparation), the low nibble comes first.  Returns the number
+ * of entries, -1 for an index above 15, -2 if an explicit zero is needed and no
+ * centroid is zero. */
+long long oracle_codebook_csr(const unsigned char* index, const float* centroids,
+                              const unsigned char* mask, int K, int L,
+                              uint16_t* centroid_bits, unsigned char* packed, float* values)
+{
+    int zero = -1;
+    for (int i = 0; i < 16; ++i) {
+        centroid_bits[i] = oracle_f32_to_f16(centroids[i]);
+        if (zero < 0 && (centroid_bits[i] & 0x7fffu) == 0) zero = i;
+    }
+    long long t = 0;
+    for (int k = 0; k < K; ++k)
+        for (int j = 0; j < L; ++j) {
+            unsigned char m = mask[(size_t)k * L + j];
+            if (!m) continue;
+            int code;
+            if (m == 2) {
+                if (zero < 0) return -2;
+                code = zero;
+            } else {
+                code = index[(size_t)k * L + j];
+                if (code > 15) return -1;
+            }
+            if (t % 2 == 0) packed[t / 2] = (unsigned char)code;
+            else packed[t / 2] = (unsigned char)(packed[t / 2] | (code << 4));
+            values[t] = oracle_f16_to_f32(centroid_bits[code]);
+            ++t;
+        }
+    return t;
 }
 
 /* Unified non-zero count (section 7): every row is brought up to the count of

@@ -361,3 +361,72 @@ def test_relu_and_maxpool():
     mp = oracle.maxpool2(x)
     ref = x[:, :, :6, :6].reshape(2, 3, 3, 2, 3, 2).max(axis=(3, 5))
     assert np.array_equal(mp, ref)
+
+
+# ------------------------------------------------------------------ cluster-quantised weights (sections 6, 9)
+
+def _numpy_codebook(index, centroids, mask):
+    """Independent statement: stored values are the binary16 centroids picked by the kept indices, row-major."""
+    c16 = np.asarray(centroids, dtype=np.float32).astype(np.float16)
+    keep = np.asarray(mask).reshape(-1) != 0
+    codes = np.asarray(index).reshape(-1)[keep].astype(np.uint8)
+    padded = np.concatenate([codes, np.zeros(codes.size % 2, dtype=np.uint8)])
+    packed = (padded[0::2] | (padded[1::2] << 4)).astype(np.uint8)
+    return c16.view(np.uint16), packed, c16.astype(np.float32)[codes]
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_codebook_csr_matches_numpy(seed):
+    rng = np.random.default_rng(600 + seed)
+    K, C, R, S = int(rng.integers(1, 9)), int(rng.integers(1, 7)), int(rng.integers(1, 4)), int(rng.integers(1, 4))
+    index = rng.integers(0, 16, (K, C, R, S)).astype(np.uint8)
+    centroids = (rng.standard_normal(16) * 10.0 ** rng.integers(-6, 3)).astype(np.float32)   # incl. half subnormals
+    mask = (rng.random((K, C, R, S)) < 0.4).astype(np.uint8)
+    rowptr, colidx, packed, bits, values = oracle.codebook_csr_encode(index, centroids, mask)
+    want_bits, want_packed, want_values = _numpy_codebook(index, centroids, mask)
+    assert np.array_equal(bits, want_bits)
+    assert np.array_equal(packed, want_packed)
+    assert np.array_equal(values.view(np.uint32), want_values.view(np.uint32))
+    # rows and columns are those of the plain encoder on any weights with that mask
+    r2, c2, _ = oracle.csr_encode(np.ones((K, C, R, S), np.float32), mask)
+    assert np.array_equal(rowptr, r2) and np.array_equal(colidx, c2)
+
+
+def test_codebook_worked_example():
+    # two output channels of 1x2x2 weights; centroids 0: -1, 1: 0, 2: 0.5, 3: 2, 4: 0.1 (not a half), rest unused
+    centroids = np.zeros(16, np.float32)
+    centroids[:5] = [-1.0, 0.0, 0.5, 2.0, 0.1]
+    index = np.array([[3, 0, 2, 4], [2, 2, 15, 0]], np.uint8).reshape(2, 1, 2, 2)
+    mask = np.array([[1, 0, 1, 1], [0, 1, 0, 1]], np.uint8).reshape(2, 1, 2, 2)
+    rowptr, colidx, packed, bits, values = oracle.codebook_csr_encode(index, centroids, mask)
+    assert rowptr.tolist() == [0, 3, 5] and colidx.tolist() == [0, 2, 3, 1, 3]
+    # codes in stored order 3,2,4,2,0 -> bytes (3 | 2<<4), (4 | 2<<4), (0)
+    assert packed.tolist() == [0x23, 0x24, 0x00]
+    assert bits[:4].tolist() == [0xBC00, 0x0000, 0x3800, 0x4000]
+    assert values.tolist() == [2.0, 0.5, float(np.float16(0.1)), 0.5, -1.0]
+    # an explicit zero of the unify step takes the first zero centroid (number 1 here)
+    m2 = mask.copy()
+    m2[1, 0, 0, 0] = 2
+    _, colidx2, packed2, _, values2 = oracle.codebook_csr_encode(index, centroids, m2)
+    assert colidx2.tolist() == [0, 2, 3, 0, 1, 3] and packed2.tolist() == [0x23, 0x14, 0x02]
+    assert values2.tolist() == [2.0, 0.5, float(np.float16(0.1)), 0.0, 0.5, -1.0]
+    with pytest.raises(ValueError):
+        oracle.codebook_csr_encode(index, np.arange(1, 17, dtype=np.float32), m2)    # no zero centroid
+    bad = index.copy()
+    bad[0, 0, 0, 0] = 16
+    with pytest.raises(ValueError):
+        oracle.codebook_csr_encode(bad, centroids, mask)
+
+
+def test_codebook_convolution_is_the_convolution_of_the_decoded_weights():
+    rng = np.random.default_rng(77)
+    N, C, K, R, S, H, W = 2, 5, 6, 3, 3, 7, 6
+    index = rng.integers(0, 16, (K, C, R, S)).astype(np.uint8)
+    centroids = np.sort(rng.standard_normal(16)).astype(np.float32)
+    mask = (rng.random((K, C, R, S)) < 0.3).astype(np.uint8)
+    x = rng.standard_normal((N, C, H, W)).astype(np.float32)
+    rowptr, colidx, _, _, values = oracle.codebook_csr_encode(index, centroids, mask)
+    got = oracle.sparse_conv((rowptr, colidx, values), x, K, R, S, 1, 1)
+    dense = centroids.astype(np.float16).astype(np.float32)[index]
+    want = oracle.dense_conv7(dense, mask, x, 1, 1)
+    assert np.array_equal(got, want)
