@@ -103,6 +103,34 @@ int sparse_conv_get_csr(sparse_conv_t h, int* K, long long* nnz,
                         const int** rowptr, const int** colidx, const void** values);
 
 /*
+ * sparse_conv_create_codebook - the same for cluster-quantised weights (section 6;
+ * section 9 uses 16 centroids of 16 bits, i.e. a 4-bit code per weight).
+ *   index      HOST, unsigned char [K][C][R][S], the centroid number (0..15) of
+ *              every weight; read only where mask is non-zero.
+ *   centroids  HOST, fp32 [16]; each is rounded to binary16 (round to nearest
+ *              even) and that value is the weight, for SC_F32 layers too.
+ *   mask, K..S, dtype, flags   as for sparse_conv_create.  With
+ *              SC_FLAG_UNIFY_NNZ the explicit zeros take the number of the first
+ *              centroid that is zero.
+ * The handle stores rowptr, colidx (as above), the codes of the stored entries in
+ * CSR order, two to a byte (entry 2i in the low nibble of byte i, entry 2i+1 in the
+ * high nibble, an unused last nibble zero) and the 16 centroids: 0.5 byte per
+ * stored weight instead of 2 or 4.  sparse_conv_get_csr returns the decoded
+ * values.  The device plan is built from the decoded values, so the forward
+ * path and its launch configuration do not differ from an uncoded layer's.
+ * SC_EINVAL: bad arguments, an index above 15 under the mask, or explicit zeros
+ * are needed and no centroid is zero.
+ */
+int sparse_conv_create_codebook(sparse_conv_t* out, const unsigned char* index, const float* centroids,
+                                const unsigned char* mask, int K, int C, int R, int S, int dtype, unsigned flags);
+
+/* Codes and centroids of a handle made by sparse_conv_create_codebook: *codes is
+ * HOST unsigned char [(nnz + 1) / 2], *centroids HOST binary16 patterns [16];
+ * both stay owned by the handle.  Either pointer may be NULL.  SC_EINVAL for a
+ * handle without a codebook. */
+int sparse_conv_get_codebook(sparse_conv_t h, const unsigned char** codes, const unsigned short** centroids);
+
+/*
  * sparse_conv_set_launch - override the per-layer launch configuration, this
  * library's counterpart of the per-layer thread-block count the paper tunes
  * (section 8, subBatchSize; section 9).  params[0..nparams) are, in order:

@@ -25,6 +25,7 @@ LIB_PATH = os.environ.get("SPARSECONV_LIBRARY") or os.path.join(
 EXPORTS = (
     "sparse_conv_create", "sparse_conv_output_shape", "sparse_conv_forward",
     "sparse_conv_get_csr", "sparse_conv_set_launch", "sparse_conv_get_launch", "sparse_conv_set_epilogue", "sparse_conv_autotune",
+    "sparse_conv_create_codebook", "sparse_conv_get_codebook",
     "sparse_conv_last_hip_error", "sparse_conv_strerror", "sparse_conv_destroy",
 )
 
@@ -49,6 +50,9 @@ def _load():
     lib = C.CDLL(LIB_PATH)
     vp, ip = C.c_void_p, C.POINTER(C.c_int)
     lib.sparse_conv_create.argtypes = [C.POINTER(vp), vp, vp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_uint]
+    lib.sparse_conv_create_codebook.argtypes = [C.POINTER(vp), vp, vp, vp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
+                                                C.c_uint]
+    lib.sparse_conv_get_codebook.argtypes = [vp, C.POINTER(vp), C.POINTER(vp)]
     lib.sparse_conv_output_shape.argtypes = [vp, C.c_int, C.c_int, C.c_int, C.c_int, ip, ip]
     lib.sparse_conv_forward.argtypes = [vp, vp, vp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, vp]
     lib.sparse_conv_get_csr.argtypes = [vp, ip, C.POINTER(C.c_longlong), C.POINTER(vp), C.POINTER(vp), C.POINTER(vp)]
@@ -91,6 +95,34 @@ def sparse_conv_create(dense_w: np.ndarray, mask: np.ndarray, dtype: int = SC_F3
     _check(_lib.sparse_conv_create(C.byref(h), w.ctypes.data, m.ctypes.data, K, Cc, R, S, dtype, flags),
            "sparse_conv_create")
     return h.value
+
+
+def sparse_conv_create_codebook(index: np.ndarray, centroids: np.ndarray, mask: np.ndarray, dtype: int = SC_F32,
+                                flags: int = 0) -> int:
+    """Handle for a cluster-quantised layer: HOST uint8 centroid numbers [K][C][R][S] (0..15), fp32 centroids [16]
+    (stored as binary16) and the uint8 mask."""
+    idx = np.ascontiguousarray(index, dtype=np.uint8)
+    cen = np.ascontiguousarray(centroids, dtype=np.float32)
+    m = np.ascontiguousarray(mask, dtype=np.uint8)
+    if idx.ndim != 4 or m.shape != idx.shape or cen.shape != (16,):
+        raise ValueError("index and mask must both be [K][C][R][S], centroids [16]")
+    K, Cc, R, S = idx.shape
+    h = C.c_void_p()
+    _check(_lib.sparse_conv_create_codebook(C.byref(h), idx.ctypes.data, cen.ctypes.data, m.ctypes.data, K, Cc, R, S,
+                                            dtype, flags), "sparse_conv_create_codebook")
+    return h.value
+
+
+def sparse_conv_get_codebook(handle: int) -> Tuple[np.ndarray, np.ndarray]:
+    """(packed 4-bit codes uint8 [(nnz + 1) // 2], centroid binary16 bits uint16 [16]) of a codebook handle (copies)."""
+    nnz = C.c_longlong()
+    _check(_lib.sparse_conv_get_csr(handle, None, C.byref(nnz), None, None, None), "sparse_conv_get_csr", handle)
+    codes, cen = C.c_void_p(), C.c_void_p()
+    _check(_lib.sparse_conv_get_codebook(handle, C.byref(codes), C.byref(cen)), "sparse_conv_get_codebook", handle)
+    nbytes = (nnz.value + 1) // 2
+    packed = np.ctypeslib.as_array(C.cast(codes, C.POINTER(C.c_uint8)), (nbytes,)).copy() if nbytes else np.zeros(0, np.uint8)
+    bits = np.ctypeslib.as_array(C.cast(cen, C.POINTER(C.c_uint16)), (16,)).copy()
+    return packed, bits
 
 
 def sparse_conv_output_shape(handle: int, H: int, W: int, stride: int, pad: int) -> Tuple[int, int]:
@@ -173,8 +205,21 @@ class SparseConv:
         self.K, self.C, self.R, self.S = dense_w.shape
         self.handle = sparse_conv_create(dense_w, mask, self.dtype, SC_FLAG_UNIFY_NNZ if unify else 0)
 
+    @classmethod
+    def from_codebook(cls, index: np.ndarray, centroids: np.ndarray, mask: np.ndarray, dtype: str = "f32",
+                      unify: bool = False) -> "SparseConv":
+        """A layer whose weights are 4-bit centroid numbers into 16 binary16 centroids."""
+        self = cls.__new__(cls)
+        self.dtype = SC_F16 if dtype in ("f16", SC_F16) else SC_F32
+        self.K, self.C, self.R, self.S = index.shape
+        self.handle = sparse_conv_create_codebook(index, centroids, mask, self.dtype, SC_FLAG_UNIFY_NNZ if unify else 0)
+        return self
+
     def csr(self):
         return sparse_conv_get_csr(self.handle, self.dtype)
+
+    def codebook(self):
+        return sparse_conv_get_codebook(self.handle)
 
     def output_shape(self, H: int, W: int, stride: int = 1, pad: int = 0):
         return sparse_conv_output_shape(self.handle, H, W, stride, pad)

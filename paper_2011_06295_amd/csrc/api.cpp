@@ -105,6 +105,38 @@ int sparse_conv_create(sparse_conv_t* out, const float* dense_w, const unsigned 
     }
 }
 
+int sparse_conv_create_codebook(sparse_conv_t* out, const unsigned char* index, const float* centroids,
+                                const unsigned char* mask, int K, int C, int R, int S, int dtype, unsigned flags)
+{
+    if (!out || !index || !centroids || !mask) return SC_EINVAL;
+    if (K <= 0 || C <= 0 || R <= 0 || S <= 0) return SC_EINVAL;
+    if (dtype != SC_F32 && dtype != SC_F16) return SC_EINVAL;
+    if (flags & ~static_cast<unsigned>(SC_FLAG_UNIFY_NNZ)) return SC_EINVAL;
+    const long long L = (long long)C * R * S;
+    if (L >= (1ll << 31)) return SC_EINVAL;
+    try {
+        std::unique_ptr<sparse_conv_s> h(new sparse_conv_s());
+        h->K = K; h->C = C; h->R = R; h->S = S; h->L = (int)L;
+        h->dtype = dtype;
+        h->flags = flags;
+        const int rc = sc::encode_csr_codebook(index, centroids, mask, K, (int)L, (flags & SC_FLAG_UNIFY_NNZ) != 0,
+                                               dtype == SC_F16, h->csr);
+        if (rc != SC_OK) return rc;
+        *out = h.release();
+        return SC_OK;
+    } catch (...) {
+        return SC_ENOMEM;
+    }
+}
+
+int sparse_conv_get_codebook(sparse_conv_t h, const unsigned char** codes, const unsigned short** centroids)
+{
+    if (!h || !h->csr.coded) return SC_EINVAL;
+    if (codes) *codes = h->csr.code.data();
+    if (centroids) *centroids = h->csr.centroid;
+    return SC_OK;
+}
+
 int sparse_conv_output_shape(sparse_conv_t h, int H, int W, int stride, int pad, int* E, int* F)
 {
     if (!h || !E || !F) return SC_EINVAL;

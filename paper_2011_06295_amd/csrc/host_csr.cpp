@@ -1,6 +1,9 @@
 // Host side of sparse_conv_create: CSR of the pruned weights (section 7 of
-// arXiv 2011.06295) and the binary16 conversion of the value array (section 8).
+// arXiv 2011.06295), the binary16 conversion of the value array (section 8) and
+// the 4-bit codebook form of cluster-quantised weights (sections 6 and 9).
 #include "internal.h"
+
+#include "../../include/sparse_conv.h"
 
 #include <algorithm>
 #include <cstring>
@@ -49,7 +52,13 @@ float half_to_float(uint16_t h)
     return u2f(sign | ((em << 13) + 0x38000000u));
 }
 
-bool encode_csr(const float* w, const unsigned char* mask, int K, int L, bool unify, bool half, Csr& out)
+namespace {
+
+// Which columns of every row are stored (section 7), row by row in ascending column
+// order: emit(k, j, explicit_zero) is called once per stored entry.  Returns false if
+// the total would not fit int32.
+template <typename Emit>
+bool encode_rows(const unsigned char* mask, int K, int L, bool unify, Csr& out, Emit emit)
 {
     out.K = K;
     out.L = L;
@@ -69,13 +78,10 @@ bool encode_csr(const float* w, const unsigned char* mask, int K, int L, bool un
     out.rowptr.assign(K + 1, 0);
     out.colidx.clear();
     out.colidx.reserve(static_cast<size_t>(total));
-    out.val32.clear();
-    out.val32.reserve(static_cast<size_t>(total));
 
     std::vector<unsigned char> state;  // per column of the current row: 0 dropped, 1 kept, 2 explicit zero
     for (int k = 0; k < K; ++k) {
         const unsigned char* m = mask + static_cast<size_t>(k) * L;
-        const float* wr = w + static_cast<size_t>(k) * L;
         state.assign(m, m + L);
         for (auto& s : state) s = s ? 1 : 0;
         if (unify) {
@@ -96,11 +102,25 @@ bool encode_csr(const float* w, const unsigned char* mask, int K, int L, bool un
         for (int j = 0; j < L; ++j) {
             if (state[j] == 0) continue;
             out.colidx.push_back(j);
-            out.val32.push_back(0.0f);
-            if (state[j] == 1) std::memcpy(&out.val32.back(), wr + j, 4);  // bit copy: NaN payloads and -0.0 survive
+            emit(k, j, state[j] == 2);
         }
         out.rowptr[k + 1] = static_cast<int>(out.colidx.size());
     }
+    return true;
+}
+
+}  // namespace
+
+bool encode_csr(const float* w, const unsigned char* mask, int K, int L, bool unify, bool half, Csr& out)
+{
+    out.val32.clear();
+    out.coded = false;
+    out.code.clear();
+    if (!encode_rows(mask, K, L, unify, out, [&](int k, int j, bool zero) {
+            out.val32.push_back(0.0f);
+            if (!zero) std::memcpy(&out.val32.back(), w + static_cast<size_t>(k) * L + j, 4);  // bit copy: NaN payloads and -0.0 survive
+        }))
+        return false;
     out.val16.clear();
     if (half) {
         out.val16.resize(out.val32.size());
@@ -110,6 +130,37 @@ bool encode_csr(const float* w, const unsigned char* mask, int K, int L, bool un
         }
     }
     return true;
+}
+
+int encode_csr_codebook(const unsigned char* index, const float* centroids, const unsigned char* mask,
+                        int K, int L, bool unify, bool half, Csr& out)
+{
+    int zero = -1;
+    float widened[16];
+    for (int i = 0; i < 16; ++i) {
+        out.centroid[i] = float_to_half_rne(centroids[i]);
+        widened[i] = half_to_float(out.centroid[i]);
+        if (zero < 0 && (out.centroid[i] & 0x7fffu) == 0) zero = i;
+    }
+    out.coded = true;
+    out.code.clear();
+    out.val32.clear();
+    out.val16.clear();
+    bool bad = false;
+    const bool fits = encode_rows(mask, K, L, unify, out, [&](int k, int j, bool explicit_zero) {
+        int c = explicit_zero ? zero : index[static_cast<size_t>(k) * L + j];
+        if (c < 0 || c > 15) {
+            bad = true;
+            c = 0;
+        }
+        const size_t t = out.val32.size();
+        if (t % 2 == 0) out.code.push_back(static_cast<uint8_t>(c));
+        else out.code.back() = static_cast<uint8_t>(out.code.back() | (c << 4));
+        out.val32.push_back(widened[c]);
+        if (half) out.val16.push_back(out.centroid[c]);
+    });
+    if (!fits || bad) return SC_EINVAL;
+    return SC_OK;
 }
 
 }  // namespace sc

@@ -19,6 +19,11 @@ struct Csr {
     std::vector<int> colidx;       // [nnz], ascending inside a row
     std::vector<float> val32;      // stored values (for SC_F16: the binary16 values widened exactly)
     std::vector<uint16_t> val16;   // binary16 patterns, SC_F16 only
+    // cluster-quantised layers only: 4-bit centroid numbers of the stored entries, two to a
+    // byte (entry 2i in the low nibble), and the 16 centroids as binary16
+    bool coded = false;
+    std::vector<uint8_t> code;
+    uint16_t centroid[16] = {};
 };
 
 uint16_t float_to_half_rne(float f);
@@ -27,6 +32,13 @@ float half_to_float(uint16_t h);
 // Encodes w*mask row by row; with unify every row is extended with explicit
 // zeros to the count of the fullest row.  Returns false if nnz would not fit int32.
 bool encode_csr(const float* w, const unsigned char* mask, int K, int L, bool unify, bool half, Csr& out);
+
+// The same for cluster-quantised weights: index [K][L] holds centroid numbers 0..15,
+// centroids[16] are rounded to binary16; the stored value of an entry is its centroid
+// (an explicit zero of the unify step: the first centroid that is zero).
+// Returns an SC_* status (SC_EINVAL: an index above 15, or a zero is needed and no centroid is zero).
+int encode_csr_codebook(const unsigned char* index, const float* centroids, const unsigned char* mask,
+                        int K, int L, bool unify, bool half, Csr& out);
 
 // ---------------------------------------------------------------- launch configuration
 

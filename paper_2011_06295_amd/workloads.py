@@ -159,6 +159,19 @@ def make_weights(config: int, layer: int, spec: LayerSpec) -> np.ndarray:
     return w.astype(np.float32)
 
 
+def make_codebook(config: int, layer: int, spec: LayerSpec, with_zero: bool = False):
+    """Stand-in for a cluster-quantised layer (the paper's 4-bit configuration: 16 centroids): centroid
+    numbers uint8 [K][C][R][S] drawn uniformly and 16 sorted centroids fp32 drawn like the weights
+    (with_zero: the one nearest to zero is set to zero, as a layer that is to be unified needs)."""
+    rng = np.random.Generator(np.random.PCG64(seed_for(config, layer) + 700))
+    std = spec.w_std if spec.w_std is not None else float(np.sqrt(2.0 / spec.row_nnz))
+    centroids = np.sort(rng.standard_normal(16) * std).astype(np.float32)
+    if with_zero:
+        centroids[int(np.argmin(np.abs(centroids)))] = 0.0
+    index = rng.integers(0, 16, (spec.K, spec.C, spec.R, spec.S)).astype(np.uint8)
+    return index, centroids
+
+
 def make_input(wl: Workload, N: Optional[int] = None) -> np.ndarray:
     """fp32 input feature maps [N][C][H][W] of the first layer."""
     rng = np.random.Generator(np.random.PCG64(seed_for(wl.config, 900)))

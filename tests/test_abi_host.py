@@ -123,3 +123,53 @@ def test_launch_plans_fit_the_hardware():
             assert 0 < p["lds_bytes"] <= 160 * 1024
             assert p["grid"] >= 1
             layer.close()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+@pytest.mark.parametrize("unify", [False, True])
+def test_codebook_csr_is_the_oracles(dtype, unify):
+    """Sections 6 and 9: 4-bit centroid numbers into 16 binary16 centroids; everything stored is bit-exact."""
+    from paper_2011_06295_amd import workloads as wl
+    spec = wl.LayerSpec("cb", C=7, K=9, R=3, S=3, H=8, W=8, stride=1, pad=1, sparsity_bp=7000)
+    index, centroids = wl.make_codebook(1, 3, spec, with_zero=unify)
+    rng = np.random.default_rng(31)
+    mask = (rng.random(index.shape) < 0.3).astype(np.uint8)
+    mask[4] = 0                                   # an empty row
+    layer = B.SparseConv.from_codebook(index, centroids, mask, dtype=dtype, unify=unify)
+    omask = oracle.unify_mask(mask)[0] if unify else mask
+    rowptr, colidx, packed, bits, values = oracle.codebook_csr_encode(index, centroids, omask)
+    rp, ci, va = layer.csr()
+    codes, cbits = layer.codebook()
+    assert np.array_equal(rp, rowptr) and np.array_equal(ci, colidx)
+    assert np.array_equal(codes, packed) and np.array_equal(cbits, bits)
+    if dtype == "f16":
+        assert np.array_equal(va, oracle.f32_to_f16_bits(values))
+    else:
+        assert np.array_equal(va.view(np.uint32), values.view(np.uint32))
+    layer.close()
+
+
+def test_codebook_argument_checks():
+    lib = B.raw_library()
+    index = np.zeros((2, 1, 2, 2), np.uint8)
+    mask = np.ones((2, 1, 2, 2), np.uint8)
+    mask[1, 0, 1, :] = 0
+    cen = np.arange(1, 17, dtype=np.float32)      # no zero centroid
+    h = C.c_void_p()
+    args = (index.ctypes.data, cen.ctypes.data, mask.ctypes.data, 2, 1, 2, 2)
+    assert lib.sparse_conv_create_codebook(C.byref(h), None, cen.ctypes.data, mask.ctypes.data, 2, 1, 2, 2, B.SC_F32, 0) == B.SC_EINVAL
+    assert lib.sparse_conv_create_codebook(C.byref(h), *args, 7, 0) == B.SC_EINVAL                       # unknown dtype
+    assert lib.sparse_conv_create_codebook(C.byref(h), *args, B.SC_F32, B.SC_FLAG_UNIFY_NNZ) == B.SC_EINVAL   # zeros needed, none in the codebook
+    assert lib.sparse_conv_create_codebook(C.byref(h), *args, B.SC_F32, 0) == B.SC_OK
+    assert lib.sparse_conv_get_codebook(h, None, None) == B.SC_OK
+    lib.sparse_conv_destroy(h)
+    index[0, 0, 0, 0] = 16
+    assert lib.sparse_conv_create_codebook(C.byref(h), *args, B.SC_F32, 0) == B.SC_EINVAL                # index above 15
+    index[0, 0, 0, 0] = 200
+    mask[0, 0, 0, 0] = 0
+    assert lib.sparse_conv_create_codebook(C.byref(h), *args, B.SC_F32, 0) == B.SC_OK                    # not read where the mask is zero
+    lib.sparse_conv_destroy(h)
+    w = np.ones((2, 1, 2, 2), np.float32)
+    plain = B.SparseConv(w, mask)
+    assert lib.sparse_conv_get_codebook(plain.handle, None, None) == B.SC_EINVAL                        # no codebook in this handle
+    plain.close()

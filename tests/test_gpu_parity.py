@@ -199,6 +199,28 @@ def test_measured_launch_choice_keeps_the_result(dtype):
     layer.close()
 
 
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+@pytest.mark.parametrize("unify", [False, True])
+def test_cluster_quantised_weights(dtype, unify):
+    """Sections 6 and 9: weights given as 4-bit centroid numbers; the result is the convolution with the
+    binary16 centroids in their place."""
+    import oracle
+    from paper_2011_06295_amd import binding as B, workloads as wl
+    spec = wl.LayerSpec("cb", C=19, K=33, R=3, S=3, H=11, W=9, stride=1, pad=1, sparsity_bp=8000)
+    index, centroids = wl.make_codebook(2, 5, spec, with_zero=unify)
+    rng = np.random.default_rng(808)
+    mask = (rng.random(index.shape) < 0.2).astype(np.uint8)
+    x = rng.standard_normal((6, spec.C, spec.H, spec.W)).astype(np.float32)
+    omask = oracle.unify_mask(mask)[0] if unify else mask
+    rowptr, colidx, _, _, values = oracle.codebook_csr_encode(index, centroids, omask)
+    xin = oracle.round_through_f16(x) if dtype == "f16" else x
+    ref = oracle.sparse_conv((rowptr, colidx, values), xin, spec.K, 3, 3, 1, 1)
+    layer = B.SparseConv.from_codebook(index, centroids, mask, dtype=dtype, unify=unify)
+    got = run_gpu(layer, x, 1, 1, dtype)
+    assert_close(got, ref, TOL[dtype], f"codebook-{dtype}-unify{unify}")
+    layer.close()
+
+
 def test_hand_examples_on_gpu():
     import json
     import os
