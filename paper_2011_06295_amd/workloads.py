@@ -172,6 +172,12 @@ def make_codebook(config: int, layer: int, spec: LayerSpec, with_zero: bool = Fa
     return index, centroids
 
 
+def pattern_value(flat_index):
+    """Input value at a flat element index for tensors too large to draw and copy: a fixed pattern of
+    251 small dyadic values, exact in binary16 and fp32 (works on numpy arrays and torch tensors alike)."""
+    return ((flat_index % 251) - 125) / 64.0
+
+
 def make_input(wl: Workload, N: Optional[int] = None) -> np.ndarray:
     """fp32 input feature maps [N][C][H][W] of the first layer."""
     rng = np.random.Generator(np.random.PCG64(seed_for(wl.config, 900)))

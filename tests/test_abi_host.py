@@ -173,3 +173,23 @@ def test_codebook_argument_checks():
     plain = B.SparseConv(w, mask)
     assert lib.sparse_conv_get_codebook(plain.handle, None, None) == B.SC_EINVAL                        # no codebook in this handle
     plain.close()
+
+
+def test_sizes_beyond_the_kernels_index_range_are_refused():
+    """Positions and tensor elements are 32-bit in the kernels: larger problems are reported, not run."""
+    lib = B.raw_library()
+    w = np.ones((2, 1, 3, 3), np.float32)
+    m = np.ones((2, 1, 3, 3), np.uint8)
+    layer = B.SparseConv(w, m)
+    out = (C.c_int * 11)()
+    # 2^22 images of 64x64: more than 2^31 lattice positions whatever the interleave
+    assert lib.sparse_conv_get_launch(layer.handle, 1 << 22, 64, 64, 1, 1, out) == B.SC_EUNSUPPORTED
+    # 70000 images of 181x181: the lattice fits, the input tensor has more than 2^31 elements;
+    # refused before the (fake) device pointers are touched
+    assert lib.sparse_conv_get_launch(layer.handle, 70000, 181, 181, 1, 1, out) == B.SC_OK
+    assert lib.sparse_conv_forward(layer.handle, 256, 512, 70000, 181, 181, 1, 1, None) == B.SC_EUNSUPPORTED
+    assert lib.sparse_conv_forward(layer.handle, 256, 512, 65551, 181, 181, 1, 1, None) == B.SC_EUNSUPPORTED   # 2^31 + 32663 elements
+    # the largest batch of such images that still fits is accepted by the planner
+    assert lib.sparse_conv_get_launch(layer.handle, 65550, 181, 181, 1, 1, out) == B.SC_OK
+    assert out[8] % 64 == 0 and 0 < out[7] <= 160 * 1024
+    layer.close()

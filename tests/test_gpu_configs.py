@@ -154,6 +154,34 @@ def test_imagenet_sized_vgg_layers_sampled(dtype):
     net.close()
 
 
+def test_largest_tensors_sampled_images():
+    """Input and output just under 2^31 elements (the kernels' index range): 65550 images of 181x181,
+    one channel in, one out.  Whole images are compared with the oracle at both ends of the batch and
+    around the 2^30-element and 2^31-byte marks."""
+    import torch
+    from paper_2011_06295_amd import binding as B, workloads as wl
+    N, H, W = 65550, 181, 181
+    assert N * H * W < 2 ** 31 <= (N + 1) * H * W
+    w = np.array([[0.5, -1.0, 0.25], [2.0, 1.0, -0.5], [0.125, -2.0, 4.0]], np.float32).reshape(1, 1, 3, 3)
+    m = np.array([[1, 0, 1], [1, 1, 0], [0, 1, 1]], np.uint8).reshape(1, 1, 3, 3)
+    layer = B.SparseConv(w, m, "f32")
+    idx = torch.arange(N * H * W, dtype=torch.int64, device="cuda")
+    x = wl.pattern_value(idx).to(torch.float32).reshape(N, 1, H, W)
+    del idx
+    y = layer.forward(x, 1, 1)
+    torch.cuda.synchronize()
+    csr = oracle.csr_encode(w, m)
+    per_image = H * W
+    picks = sorted({0, 1, 2, 3, N - 1, N - 2, N - 3, N - 4, 2 ** 30 // per_image, 2 ** 30 // per_image + 1,
+                    2 ** 29 // per_image, 2 ** 29 // per_image + 1, N // 2, 12345})
+    for n in picks:
+        xi = wl.pattern_value(np.arange(n * per_image, (n + 1) * per_image, dtype=np.int64)).astype(np.float32)
+        assert np.array_equal(xi, x[n].reshape(-1).cpu().numpy())
+        ref = oracle.sparse_conv(csr, xi.reshape(1, 1, H, W), 1, 3, 3, 1, 1)
+        assert_close(y[n:n + 1].cpu().numpy(), ref, TOL["f32"], f"largest-image{n}")
+    layer.close()
+
+
 def test_dense_comparison_routes_every_layer():
     """The dense platform convolution on the masked weights gives the same numbers, and the
     dispatcher names one of the two implementations per layer."""
