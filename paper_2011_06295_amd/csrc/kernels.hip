@@ -430,13 +430,14 @@ __global__ __launch_bounds__(1024) void tile_kernel(const KernelArgs a)
         }
     };
 
-    unsigned warm = touch();  // chunk 0's entries
-    begin_chunk(0);
     __syncthreads();  // slot table complete
     prepare_units();
     fetch_begin(0);
 #pragma unroll
     for (int t = 0; t < kStage; ++t) fetch_unit(t);
+    // the input loads do not wait for the descriptor (requested at the top); what needs it comes after them
+    unsigned warm = touch();  // chunk 0's entries
+    begin_chunk(0);
     // while the first loads are in flight: padding rows/columns and absent images are zeroed
     // once and stay zero for the whole kernel (staging writes real elements only)
     for (int u = tid; u < reject; u += nthreads) tile[u] = VT::zero();
