@@ -295,37 +295,64 @@ int build_plan(const Csr& csr, int C, int R, int S, int elem_bytes, const Geomet
     p.grid = (int)grid;
 
     // ---- tables
-    // Output channel of every accumulator slot (kb, wk, kk).  Rows of equal length (the paper's
-    // unified count) keep their order.  Ragged rows are dealt out longest first, back and forth
-    // over all wavefronts of all channel blocks, so that wavefronts and workgroups get about
-    // the same number of stored weights.
+    const int RS = R * S;
+    const int nchunks = p.nchunks;
+    // Output channel of every accumulator slot (kb, wk, kk).  The wavefronts of a workgroup meet
+    // at a barrier after every channel chunk, so what should be equal among them is the number
+    // of batches per chunk, not only per layer (a row's weights are spread unevenly over the
+    // chunks even when all rows have the paper's unified count).
+    //  1. Rows, longest first, are dealt back and forth over the channel blocks: every
+    //     workgroup gets about the same total, and empty slots are spread over all of them.
+    //  2. Inside a channel block each row goes to the wavefront (with a free slot) whose load
+    //     so far overlaps least with the row's own chunk profile (smallest dot product).
     p.krow.assign((size_t)p.kblocks * KB, -1);
     {
-        int lo = INT_MAX, hi = 0;
+        std::vector<int> batches((size_t)K * nchunks);   // batches of row k in chunk ch
+        std::vector<long long> total(K, 0);
         for (int k = 0; k < K; ++k) {
-            const int n = csr.rowptr[k + 1] - csr.rowptr[k];
-            lo = std::min(lo, n);
-            hi = std::max(hi, n);
+            const int* cb = csr.colidx.data() + csr.rowptr[k];
+            const int* ce = csr.colidx.data() + csr.rowptr[k + 1];
+            const int* lo = cb;
+            for (int ch = 0; ch < nchunks; ++ch) {
+                const int c1 = std::min(C, (ch + 1) * p.Cc);
+                const int* hi = std::lower_bound(lo, ce, c1 * RS);
+                batches[(size_t)k * nchunks + ch] = cdiv(hi - lo, kBatch);
+                total[k] += batches[(size_t)k * nchunks + ch];
+                lo = hi;
+            }
         }
-        if (hi == lo) {
-            for (int k = 0; k < K; ++k) p.krow[k] = k;
-        } else {
-            std::vector<int> order(K);
-            for (int k = 0; k < K; ++k) order[k] = k;
-            std::stable_sort(order.begin(), order.end(), [&](int x, int y) {
-                return csr.rowptr[x + 1] - csr.rowptr[x] > csr.rowptr[y + 1] - csr.rowptr[y];
-            });
-            const int bins = p.kblocks * p.WK;   // wavefronts over all channel blocks
-            for (int i = 0; i < K; ++i) {
-                const int round = i / bins, j = i % bins;
-                const int bin = (round & 1) ? bins - 1 - j : j;
-                p.krow[(size_t)bin * p.KW + round] = order[i];   // slot (bin = kb*WK + wk, kk = round)
+        std::vector<int> order(K);
+        for (int k = 0; k < K; ++k) order[k] = k;
+        std::stable_sort(order.begin(), order.end(), [&](int x, int y) { return total[x] > total[y]; });
+        std::vector<std::vector<int>> of_block(p.kblocks);
+        for (int i = 0; i < K; ++i) {
+            const int round = i / p.kblocks, j = i % p.kblocks;
+            of_block[(round & 1) ? p.kblocks - 1 - j : j].push_back(order[i]);
+        }
+        std::vector<long long> load((size_t)p.WK * nchunks);
+        std::vector<int> fill(p.WK);
+        for (int kb = 0; kb < p.kblocks; ++kb) {
+            std::fill(load.begin(), load.end(), 0);
+            std::fill(fill.begin(), fill.end(), 0);
+            for (int k : of_block[kb]) {   // longest first
+                const int* bk = &batches[(size_t)k * nchunks];
+                int best_w = -1;
+                long long best_dot = 0;
+                for (int w = 0; w < p.WK; ++w) {
+                    if (fill[w] >= p.KW) continue;
+                    long long dot = 0;
+                    for (int ch = 0; ch < nchunks; ++ch) dot += load[(size_t)w * nchunks + ch] * bk[ch];
+                    if (best_w < 0 || dot < best_dot || (dot == best_dot && fill[w] < fill[best_w])) {
+                        best_w = w;
+                        best_dot = dot;
+                    }
+                }
+                p.krow[((size_t)kb * p.WK + best_w) * p.KW + fill[best_w]++] = k;
+                for (int ch = 0; ch < nchunks; ++ch) load[(size_t)best_w * nchunks + ch] += bk[ch];
             }
         }
     }
 
-    const int RS = R * S;
-    const int nchunks = p.nchunks;
     const int SW = p.KW + 1;  // descriptor: first entry, then batches of each of the KW rows
     p.seg.assign(((size_t)p.kblocks * nchunks * p.WK + 1) * SW, 0);   // one terminal descriptor
     p.entries.clear();
