@@ -98,7 +98,10 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="vgg16_f32")
+    ap.add_argument("--workload", default="vgg16_f32",
+                    help="vgg16_f32 (default: VGG-16 for 32x32 images, batch 128), vgg16_f16 (batch 256), lenet5, config1, "
+                         "sweepNN / sweepNNr (256->256 14x14 layer at NN %% sparsity, unified / ragged rows), "
+                         "resnet1x1, densenet1x1, cnn1d, vgg16_224 (each also with _f16)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--launch", default="", help="comma separated launch override applied to every layer")
     ap.add_argument("--autotune", type=int, default=8,
