@@ -221,6 +221,43 @@ def test_cluster_quantised_weights(dtype, unify):
     layer.close()
 
 
+@pytest.mark.parametrize("seed", [7, 11, 23])
+def test_random_shapes_with_random_launch_overrides(seed):
+    """Random geometry (filters up to 5x5, stride 1..3, pad 0..3, maps up to 40 x 200) crossed with random
+    launch overrides, both precisions, unified or not.  Overrides the planner refuses are skipped."""
+    from paper_2011_06295_amd import binding as B
+    rng = np.random.default_rng(seed)
+    ran = 0
+    for t in range(40):
+        R, S = int(rng.integers(1, 6)), int(rng.integers(1, 6))
+        st, p = int(rng.integers(1, 4)), int(rng.integers(0, 4))
+        H, W = int(rng.integers(1, 40)), int(rng.integers(1, 200 if t % 3 == 0 else 70))
+        if H + 2 * p < R or W + 2 * p < S:
+            continue
+        N, C, K = int(rng.integers(1, 20)), int(rng.integers(1, 40)), int(rng.integers(1, 70))
+        dtype = str(rng.choice(["f32", "f16"]))
+        unify = bool(rng.integers(0, 2))
+        w, m, x = rand_layer(rng, N, C, K, R, S, H, W, density=float(rng.choice([0.02, 0.1, 0.3, 0.7])))
+        vmax = 8 if dtype == "f16" else 4
+        launch = [int(rng.choice([0, 1, 2, 4, vmax])), int(rng.choice([0, 1, 2, 3, 4])), int(rng.choice([0, 1, 2, 3, 5, 8])),
+                  int(rng.choice([0, 1, 2, 4, 8, 16])), int(rng.choice([0, 0, 1, 2, 3, 7, 16])), 0, int(rng.choice([0, 1, 2]))]
+        if rng.integers(0, 3) == 0:
+            launch = [0]
+        layer = B.SparseConv(w, m, dtype=dtype, unify=unify)
+        try:
+            layer.set_launch(launch)
+            info = layer.get_launch(N, H, W, st, p)
+        except B.SparseConvError:
+            layer.close()
+            continue
+        print(f"case {t}: {(N, C, K, R, S, H, W, st, p)} {dtype} unify={unify} launch={launch} -> {info}", flush=True)
+        got = run_gpu(layer, x, st, p, dtype)
+        assert_close(got, oracle_ref(w, m, x, st, p, dtype, unify), TOL[dtype], f"random-{seed}-{t}")
+        layer.close()
+        ran += 1
+    assert ran >= 20
+
+
 def test_hand_examples_on_gpu():
     import json
     import os
