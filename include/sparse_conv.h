@@ -88,7 +88,8 @@ int sparse_conv_output_shape(sparse_conv_t h, int H, int W, int stride, int pad,
  * Asynchronous: kernels are enqueued on the stream and the call returns
  * without synchronising.  The first call for a new (N,H,W,stride,pad) builds
  * and uploads a per-geometry plan (one synchronous allocation + copy);
- * further calls with the same geometry allocate nothing.
+ * further calls with the same geometry allocate nothing and enqueue exactly one
+ * kernel, so they may be recorded into a HIP graph on a capturing stream.
  */
 int sparse_conv_forward(sparse_conv_t h, const void* input, void* output,
                         int N, int H, int W, int stride, int pad, void* stream);

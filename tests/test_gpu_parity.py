@@ -258,6 +258,37 @@ def test_random_shapes_with_random_launch_overrides(seed):
     assert ran >= 20
 
 
+def test_forward_can_be_captured_in_a_graph():
+    """After one eager call (which uploads the plan) a forward is a single kernel launch on the caller's
+    stream: captured once and replayed on new input contents it gives what the eager call gives."""
+    import torch
+    from paper_2011_06295_amd import binding as B
+    rng = np.random.default_rng(2718)
+    N, C, K, R, S, H, W = 8, 24, 48, 3, 3, 16, 16
+    w, m, x = rand_layer(rng, N, C, K, R, S, H, W, density=0.15)
+    layer = B.SparseConv(w, m, dtype="f32")
+    layer.set_epilogue(rng.standard_normal(K).astype(np.float32), relu=True)
+    xt = torch.from_numpy(x).cuda()
+    y = layer.forward(xt, 1, 1)                      # eager: builds and uploads the plan
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        layer.forward(xt, 1, 1, out=y)               # warm-up on the capture stream
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            layer.forward(xt, 1, 1, out=y)
+    for rep in range(3):
+        xt.copy_(torch.from_numpy(rng.standard_normal(x.shape).astype(np.float32)))
+        want = layer.forward(xt, 1, 1).clone()       # eager work between the replays
+        torch.cuda.synchronize()
+        y.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(y, want), f"replay {rep}"
+    layer.close()
+
+
 def test_hand_examples_on_gpu():
     import json
     import os
