@@ -330,16 +330,23 @@ int build_plan(const Csr& csr, int C, int R, int S, int elem_bytes, const Geomet
             of_block[(round & 1) ? p.kblocks - 1 - j : j].push_back(order[i]);
         }
         std::vector<long long> load((size_t)p.WK * nchunks);
-        std::vector<int> fill(p.WK);
+        std::vector<int> fill(p.WK), room(p.WK);
         for (int kb = 0; kb < p.kblocks; ++kb) {
             std::fill(load.begin(), load.end(), 0);
             std::fill(fill.begin(), fill.end(), 0);
+            // A SIMD serves its older wavefronts first, so the last wavefronts of a workgroup are
+            // the ones the others wait for: the slots a block leaves empty are theirs.
+            std::fill(room.begin(), room.end(), p.KW);
+            for (int spare = KB - (int)of_block[kb].size(), w = p.WK - 1; spare > 0; --spare) {
+                --room[w];
+                w = w > 0 ? w - 1 : p.WK - 1;
+            }
             for (int k : of_block[kb]) {   // longest first
                 const int* bk = &batches[(size_t)k * nchunks];
                 int best_w = -1;
                 long long best_dot = 0;
                 for (int w = 0; w < p.WK; ++w) {
-                    if (fill[w] >= p.KW) continue;
+                    if (fill[w] >= room[w]) continue;
                     long long dot = 0;
                     for (int ch = 0; ch < nchunks; ++ch) dot += load[(size_t)w * nchunks + ch] * bk[ch];
                     if (best_w < 0 || dot < best_dot || (dot == best_dot && fill[w] < fill[best_w])) {
