@@ -334,12 +334,25 @@ int build_plan(const Csr& csr, int C, int R, int S, int elem_bytes, const Geomet
         for (int kb = 0; kb < p.kblocks; ++kb) {
             std::fill(load.begin(), load.end(), 0);
             std::fill(fill.begin(), fill.end(), 0);
-            // A SIMD serves its older wavefronts first, so the last wavefronts of a workgroup are
-            // the ones the others wait for: the slots a block leaves empty are theirs.
+            // The wavefronts of a workgroup go round the 4 SIMDs of a CU, and a SIMD serves its
+            // older wavefronts first: the fullest SIMD sets the pace of a chunk and its youngest
+            // wavefront is the one the others wait for.  The slots a block leaves empty are
+            // therefore taken, one at a time, from the youngest wavefront of the SIMD that still
+            // holds the most rows.
             std::fill(room.begin(), room.end(), p.KW);
-            for (int spare = KB - (int)of_block[kb].size(), w = p.WK - 1; spare > 0; --spare) {
-                --room[w];
-                w = w > 0 ? w - 1 : p.WK - 1;
+            const int waves_wg = p.WP * p.WK;   // wavefront index = wk * WP + wp
+            for (int spare = KB - (int)of_block[kb].size(); spare > 0; --spare) {
+                long long rows_on[4] = {0, 0, 0, 0};
+                for (int w = 0; w < p.WK; ++w)
+                    for (int q = 0; q < p.WP; ++q) rows_on[(w * p.WP + q) & 3] += room[w];
+                int pick = -1;
+                for (int wave = waves_wg - 1; wave >= 0; --wave) {   // youngest first
+                    const int w = wave / p.WP;
+                    if (room[w] <= 0) continue;
+                    if (pick < 0 || rows_on[wave & 3] > rows_on[(pick * p.WP + p.WP - 1) & 3]) pick = w;
+                }
+                if (pick < 0) break;
+                --room[pick];
             }
             for (int k : of_block[kb]) {   // longest first
                 const int* bk = &batches[(size_t)k * nchunks];
