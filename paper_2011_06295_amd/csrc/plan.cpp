@@ -50,6 +50,30 @@ struct Cand {
 // Tile height in lattice rows for a window of `span` positions starting anywhere in a row.
 int tile_rows(int span, int Wp, int R, int S) { return (Wp - 1 + span - 1 + (R - 1) * Wp + S - 1) / Wp + 1; }
 
+// Rows every wavefront (channel index wk) of a channel block takes when the block holds
+// `nrows` of its WK * KW slots.  The wavefronts of a workgroup go round the 4 SIMDs of a CU,
+// and a SIMD serves its older wavefronts first: the fullest SIMD sets the pace of a chunk and
+// its youngest wavefront is the one the others wait for.  The slots a block leaves empty are
+// therefore taken, one at a time, from the youngest wavefront of the SIMD that still holds
+// the most rows.  (Wavefront index = wk * WP + wp.)
+void rows_per_wavefront(int nrows, int WP, int WK, int KW, std::vector<int>& room)
+{
+    room.assign(WK, KW);
+    for (int spare = WK * KW - nrows; spare > 0; --spare) {
+        long long rows_on[4] = {0, 0, 0, 0};
+        for (int w = 0; w < WK; ++w)
+            for (int q = 0; q < WP; ++q) rows_on[(w * WP + q) & 3] += room[w];
+        int pick = -1;
+        for (int wave = WP * WK - 1; wave >= 0; --wave) {   // youngest first
+            const int w = wave / WP;
+            if (room[w] <= 0) continue;
+            if (pick < 0 || rows_on[wave & 3] > rows_on[(pick * WP + WP - 1) & 3]) pick = w;
+        }
+        if (pick < 0) break;
+        --room[pick];
+    }
+}
+
 // Rough time of one launch in CU clocks.  The structure follows measurements on
 // MI355X; the constants were fitted to the measured times of ~37000 launch
 // configurations (every shape the candidate loops below produce) of the 13
@@ -63,10 +87,12 @@ int tile_rows(int span, int Wp, int R, int S) { return (Wp - 1 + span - 1 + (R -
 //    for the address and loop control, and the CU's LDS kBatch * LP * 64 elements
 //    at ~225 B/clk.  For 16-byte fp32 elements the two are about equal, and they
 //    overlap for the most part.
-//  * A lone wavefront cannot hide its own LDS and scalar-fetch latency (~100 clocks a step).
+//  * The multiply-adds that count are those of the SIMD with the most rows (see
+//    rows_per_wavefront); the LDS reads are the whole CU's.
+//  * A lone wavefront cannot hide its own LDS and scalar-fetch latency (~170 clocks a step).
 //  * Registers (56 + accumulators + two groups of LDS reads in flight) bound the
 //    wavefronts resident on a SIMD, and with them the workgroups on a CU.
-//  * Staging moves ~16 B/clk/CU from L2 and overlaps the arithmetic except for the
+//  * Staging moves ~24 B/clk/CU from L2 and overlaps the arithmetic except for the
 //    first chunk; a workgroup costs ~7 us to start and finish, a chunk ~0.4 us.
 //  * Workgroups run in rounds of (CUs * resident workgroups); a partly filled
 //    last round still takes a round.
@@ -74,34 +100,42 @@ double estimate(const Shape& s, const Cand& c)
 {
     const int nchunks = cdiv(s.C, c.Cc);
     const double seg = s.row_nnz * c.Cc / s.C;
-    const double batches = nchunks == 1 ? std::ceil(seg / kBatch) : seg / kBatch + 0.6;
-    // measured residuals: one row per wavefront and two positions per lane run a little
-    // slower than their instruction counts say, 8 rows per wavefront too
-    const double shape_factor = (c.KW == 1 ? 1.1 : c.KW == 8 ? 1.05 : 1.0) * (c.LP == 2 ? 1.06 : 1.0);
-    const double steps_wave = c.KW * batches * nchunks * shape_factor;
+    const double batches = nchunks == 1 ? std::ceil(seg / kBatch) : seg / kBatch + 1.0;
     const int waves = c.WP * c.WK;
     const double regs = std::min(128.0, 56.0 + c.KW * c.LP * c.V + 4.0 * c.LP * (s.ub / 4.0));  // the kernels are built for <= 128
     const int per_simd = std::min(8, 512 / (8 * (int)std::ceil(regs / 8.0)));
     const int conc_max = std::min(kMaxLds / c.lds, 4 * per_simd / waves);
     if (conc_max < 1) return -1.0;
-    const long long wgs = (long long)cdiv(s.npos, (long long)kWave * c.WP * c.LP) * cdiv(s.K, c.WK * c.KW);
+    const int kblocks = cdiv(s.K, c.WK * c.KW);
+    const long long wgs = (long long)cdiv(s.npos, (long long)kWave * c.WP * c.LP) * kblocks;
+    // rows on the fullest SIMD and wavefront-rows in all of a typical channel block
+    std::vector<int> room;
+    rows_per_wavefront(cdiv(s.K, kblocks), c.WP, c.WK, c.KW, room);
+    long long rows_on[4] = {0, 0, 0, 0}, rows_all = 0;
+    for (int w = 0; w < c.WK; ++w)
+        for (int q = 0; q < c.WP; ++q) {
+            rows_on[(w * c.WP + q) & 3] += room[w];
+            rows_all += room[w];
+        }
+    const double rows_max = (double)std::max(std::max(rows_on[0], rows_on[1]), std::max(rows_on[2], rows_on[3]));
     const double fma_clk = s.elem_bytes == 2 ? 4.4 : 4.0;
     const double v_step = kBatch * (c.LP * c.V * fma_clk + 8.0);
     const double l_step = kBatch * c.LP * 64.0 * s.ub / 225.0;
     const double gbytes = (double)s.C * c.CS * s.ub * ((double)s.W / s.Wp) * std::min(1.0, (double)s.H / s.Hs);
     const double fixed = 16000.0 + 1000.0 * nchunks;
+    const double one_row_only = c.KW == 1 ? 1.2 : 1.0;   // measured residual
     double t = 0.0;
     long long remaining = wgs;
     const long long slots = (long long)kCUs * conc_max;
     while (remaining > 0) {
         const long long n = std::min(remaining, slots);
         const int conc = (int)((n + kCUs - 1) / kCUs);
-        const double W = (double)conc * waves;
-        const double a = W * v_step / 4.0, b = W * l_step;
-        const double shared = (std::max(a, b) + 0.3 * std::min(a, b)) / 0.92;
-        const double step_clk = std::max(shared, v_step + 100.0);
-        const double t_compute = steps_wave * step_clk;
-        const double t_stage = conc * gbytes / 16.0;
+        // one batch of every row of the resident workgroups: the fullest SIMD's multiply-adds, the CU's LDS reads
+        const double a = conc * rows_max * v_step, b = conc * (double)rows_all * l_step;
+        const double shared = std::max(a, b) + 0.3 * std::min(a, b);
+        const double per_batch = std::max(shared, c.KW * (v_step + 170.0));
+        const double t_compute = batches * nchunks * one_row_only * per_batch;
+        const double t_stage = conc * gbytes / 24.0;
         const long long full = remaining / slots;
         const double round = std::max(t_compute, t_stage) + t_stage / nchunks + fixed;
         if (full > 1) {            // identical full rounds
@@ -334,26 +368,7 @@ int build_plan(const Csr& csr, int C, int R, int S, int elem_bytes, const Geomet
         for (int kb = 0; kb < p.kblocks; ++kb) {
             std::fill(load.begin(), load.end(), 0);
             std::fill(fill.begin(), fill.end(), 0);
-            // The wavefronts of a workgroup go round the 4 SIMDs of a CU, and a SIMD serves its
-            // older wavefronts first: the fullest SIMD sets the pace of a chunk and its youngest
-            // wavefront is the one the others wait for.  The slots a block leaves empty are
-            // therefore taken, one at a time, from the youngest wavefront of the SIMD that still
-            // holds the most rows.
-            std::fill(room.begin(), room.end(), p.KW);
-            const int waves_wg = p.WP * p.WK;   // wavefront index = wk * WP + wp
-            for (int spare = KB - (int)of_block[kb].size(); spare > 0; --spare) {
-                long long rows_on[4] = {0, 0, 0, 0};
-                for (int w = 0; w < p.WK; ++w)
-                    for (int q = 0; q < p.WP; ++q) rows_on[(w * p.WP + q) & 3] += room[w];
-                int pick = -1;
-                for (int wave = waves_wg - 1; wave >= 0; --wave) {   // youngest first
-                    const int w = wave / p.WP;
-                    if (room[w] <= 0) continue;
-                    if (pick < 0 || rows_on[wave & 3] > rows_on[(pick * p.WP + p.WP - 1) & 3]) pick = w;
-                }
-                if (pick < 0) break;
-                --room[pick];
-            }
+            rows_per_wavefront((int)of_block[kb].size(), p.WP, p.WK, p.KW, room);   // empty slots go to the last wavefronts of the fullest SIMDs
             for (int k : of_block[kb]) {   // longest first
                 const int* bk = &batches[(size_t)k * nchunks];
                 int best_w = -1;
