@@ -142,6 +142,9 @@ int sparse_conv_get_codebook(sparse_conv_t h, const unsigned char** codes, const
  *   [4] Cc  input channels staged per LDS pass
  *   [5] LDS budget in bytes per workgroup (used when Cc is automatic)
  *   [6] LP  output positions per lane (1 or 2; with LP = 2: KW * V <= 16)
+ *   [7] channel blocks the K output channels are dealt over (a workgroup takes one
+ *           block; at least ceil(K / (WK * KW)), more leaves row slots empty on the
+ *           wavefronts a SIMD serves last; fewer is SC_EUNSUPPORTED)
  * Missing trailing entries and zeros mean "automatic".  nparams = 0 restores
  * the automatic choice.  Cached plans are discarded.  SC_EINVAL for values the
  * kernels cannot run; a configuration that cannot fit is reported by forward.
@@ -182,9 +185,9 @@ int sparse_conv_set_epilogue(sparse_conv_t h, const float* bias, unsigned flags)
 /* The launch configuration chosen for a geometry: [0] V .. [4] Cc, [5] the LDS
  * budget in force, [6] workgroups launched, [7] LDS bytes
  * per workgroup, [8] threads per workgroup, [9] stored plan entries
- * (including batch padding), [10] LP.  [0..5] are in the order of
+ * (including batch padding), [10] LP, [11] channel blocks.  [0..5] are in the order of
  * sparse_conv_set_launch.  Builds the plan's host side if needed; needs no
- * GPU.  params must have room for 11 ints. */
+ * GPU.  params must have room for 12 ints. */
 int sparse_conv_get_launch(sparse_conv_t h, int N, int H, int W, int stride, int pad, int* params);
 
 /* HIP error code of the last failing runtime call made through this handle (0 if none). */

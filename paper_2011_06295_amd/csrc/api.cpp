@@ -44,7 +44,7 @@ int get_plan(sparse_conv_s* h, const Geometry& g, Plan** out)
         std::unique_ptr<Plan> p(new (std::nothrow) Plan());
         if (!p) return SC_ENOMEM;
         const Launch& o = h->over;
-        const bool automatic = !(o.V || o.WP || o.WK || o.KW || o.Cc || o.lds_budget || o.LP);
+        const bool automatic = !(o.V || o.WP || o.WK || o.KW || o.Cc || o.lds_budget || o.LP || o.kblocks);
         auto tuned = h->tuned.find(g);
         const Launch& use = (automatic && tuned != h->tuned.end()) ? tuned->second : h->over;
         int rc = build_plan(h->csr, h->C, h->R, h->S, h->dtype == SC_F16 ? 2 : 4, g, use, *p);
@@ -162,8 +162,8 @@ int sparse_conv_get_csr(sparse_conv_t h, int* K, long long* nnz,
 
 int sparse_conv_set_launch(sparse_conv_t h, const int* params, int nparams)
 {
-    if (!h || nparams < 0 || nparams > 7 || (nparams > 0 && !params)) return SC_EINVAL;
-    int v[7] = {0, 0, 0, 0, 0, 0, 0};
+    if (!h || nparams < 0 || nparams > 8 || (nparams > 0 && !params)) return SC_EINVAL;
+    int v[8] = {0, 0, 0, 0, 0, 0, 0, 0};
     for (int i = 0; i < nparams; ++i) {
         if (params[i] < 0) return SC_EINVAL;
         v[i] = params[i];
@@ -175,7 +175,7 @@ int sparse_conv_set_launch(sparse_conv_t h, const int* params, int nparams)
     if (v[5] > 160 * 1024) return SC_EINVAL;
     if (v[6] > 2) return SC_EINVAL;
     sc::Launch l;
-    l.V = v[0]; l.WP = v[1]; l.WK = v[2]; l.KW = v[3]; l.Cc = v[4]; l.lds_budget = v[5]; l.LP = v[6];
+    l.V = v[0]; l.WP = v[1]; l.WK = v[2]; l.KW = v[3]; l.Cc = v[4]; l.lds_budget = v[5]; l.LP = v[6]; l.kblocks = v[7];
     h->over = l;
     h->plans.clear();
     h->tuned.clear();
@@ -209,8 +209,8 @@ int sparse_conv_get_launch(sparse_conv_t h, int N, int H, int W, int stride, int
         sc::Plan* p = nullptr;
         int rc = sc::get_plan(h, sc::Geometry{N, H, W, stride, pad}, &p);
         if (rc != SC_OK) return rc;
-        const int v[11] = {p->V, p->WP, p->WK, p->KW, p->Cc, h->over.lds_budget,
-                           p->grid, p->lds_bytes, p->threads, (int)p->entries.size(), p->LP};
+        const int v[12] = {p->V, p->WP, p->WK, p->KW, p->Cc, h->over.lds_budget,
+                           p->grid, p->lds_bytes, p->threads, (int)p->entries.size(), p->LP, p->kblocks};
         std::memcpy(params, v, sizeof(v));
         return SC_OK;
     } catch (...) {

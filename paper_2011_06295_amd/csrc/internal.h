@@ -51,6 +51,7 @@ struct Launch {
     int Cc = 0;   // channels per LDS pass
     int lds_budget = 0;
     int LP = 0;   // positions per lane (1 or 2)
+    int kblocks = 0;  // channel blocks (at least ceil(K / (WK * KW)); more leaves slots empty)
 };
 
 struct Geometry {

@@ -43,7 +43,7 @@ struct Shape {
 };
 
 struct Cand {
-    int V, WP, WK, KW, Cc, LP;
+    int V, WP, WK, KW, Cc, LP, kblocks;
     int Hb, CS, lds, SL, rows_mode, SG, nbuf, pitch;
 };
 
@@ -106,7 +106,7 @@ double estimate(const Shape& s, const Cand& c)
     const int per_simd = std::min(8, 512 / (8 * (int)std::ceil(regs / 8.0)));
     const int conc_max = std::min(kMaxLds / c.lds, 4 * per_simd / waves);
     if (conc_max < 1) return -1.0;
-    const int kblocks = cdiv(s.K, c.WK * c.KW);
+    const int kblocks = c.kblocks;
     const long long wgs = (long long)cdiv(s.npos, (long long)kWave * c.WP * c.LP) * kblocks;
     // rows on the fullest SIMD and wavefront-rows in all of a typical channel block
     std::vector<int> room;
@@ -262,21 +262,29 @@ int build_plan(const Csr& csr, int C, int R, int S, int elem_bytes, const Geomet
                         // tile buffer(s), one reject element, table
                         const long long lds = (((long long)nbuf * Cc * CS + 1) * s.ub + 15) / 16 * 16 + tbl;
                         if (lds > kMaxLds) continue;
-                        Cand c{V, wp, wk, kw, Cc, LP, Hb, (int)CS, (int)lds, (int)SL, banded ? 2 : rows_mode ? 1 : 0, rows_mode ? 1 : (int)GC, nbuf, pitch};
-                        double t = estimate(s, c);
-                        if (t < 0) {
-                            if (!(over.WP || over.WK || over.KW || over.Cc || over.lds_budget || over.LP)) continue;
-                            t = 1e30;   // an explicit request is honoured even where the estimate expects no residency
-                        }
-                        if (ranked) {
-                            Launch l;
-                            l.V = V; l.WP = wp; l.WK = wk; l.KW = kw; l.Cc = Cc; l.LP = LP;
-                            ranked->emplace_back(t, l);
-                        }
-                        if (best_t < 0 || t < best_t) {
-                            best_t = t;
-                            best = c;
-                            bs = s;
+                        // More channel blocks than the rows need leave slots empty, which relieves the
+                        // last wavefronts of the fullest SIMDs (rows_per_wavefront): up to two extra.
+                        const int kb_min = cdiv(K, wk * kw);
+                        for (int extra = 0; extra < 3; ++extra) {
+                            const int kblocks = over.kblocks ? over.kblocks : kb_min + extra;
+                            if (over.kblocks && extra) break;
+                            if (kblocks < kb_min || (extra && kblocks > K)) continue;
+                            Cand c{V, wp, wk, kw, Cc, LP, kblocks, Hb, (int)CS, (int)lds, (int)SL, banded ? 2 : rows_mode ? 1 : 0, rows_mode ? 1 : (int)GC, nbuf, pitch};
+                            double t = estimate(s, c);
+                            if (t < 0) {
+                                if (!(over.WP || over.WK || over.KW || over.Cc || over.lds_budget || over.LP || over.kblocks)) continue;
+                                t = 1e30;   // an explicit request is honoured even where the estimate expects no residency
+                            }
+                            if (ranked) {
+                                Launch l;
+                                l.V = V; l.WP = wp; l.WK = wk; l.KW = kw; l.Cc = Cc; l.LP = LP; l.kblocks = kblocks;
+                                ranked->emplace_back(t, l);
+                            }
+                            if (best_t < 0 || t < best_t) {
+                                best_t = t;
+                                best = c;
+                                bs = s;
+                            }
                         }
                     }
                 }
@@ -293,7 +301,7 @@ int build_plan(const Csr& csr, int C, int R, int S, int elem_bytes, const Geomet
             bool seen = false;
             for (const auto& u : uniq)
                 seen = seen || (u.second.V == e.second.V && u.second.WP == e.second.WP && u.second.WK == e.second.WK &&
-                                u.second.KW == e.second.KW && u.second.Cc == e.second.Cc && u.second.LP == e.second.LP);
+                                u.second.KW == e.second.KW && u.second.Cc == e.second.Cc && u.second.LP == e.second.LP && u.second.kblocks == e.second.kblocks);
             if (!seen) uniq.push_back(e);
             if (uniq.size() >= 64) break;
         }
@@ -313,7 +321,7 @@ int build_plan(const Csr& csr, int C, int R, int S, int elem_bytes, const Geomet
     p.npos = s.npos;
     const long long ntiles = (s.npos + p.span - 1) / p.span;
     const int KB = p.WK * p.KW;
-    p.kblocks = cdiv(K, KB);
+    p.kblocks = best.kblocks;
     p.threads = kWave * p.WP * p.WK;
     p.lds_bytes = best.lds;
     p.SL = best.SL;
