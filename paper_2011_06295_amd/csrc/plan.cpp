@@ -67,7 +67,8 @@ void rows_per_wavefront(int nrows, int WP, int WK, int KW, std::vector<int>& roo
         for (int wave = WP * WK - 1; wave >= 0; --wave) {   // youngest first
             const int w = wave / WP;
             if (room[w] <= 0) continue;
-            if (pick < 0 || rows_on[wave & 3] > rows_on[(pick * WP + WP - 1) & 3]) pick = w;
+            const long long mine = rows_on[wave & 3], best = pick < 0 ? -1 : rows_on[(pick * WP + WP - 1) & 3];
+            if (pick < 0 || mine > best || (mine == best && room[w] > room[pick])) pick = w;
         }
         if (pick < 0) break;
         --room[pick];
@@ -75,7 +76,7 @@ void rows_per_wavefront(int nrows, int WP, int WK, int KW, std::vector<int>& roo
 }
 
 // Rough time of one launch in CU clocks.  The structure follows measurements on
-// MI355X; the constants were fitted to the measured times of ~37000 launch
+// MI355X; the constants were fitted to the measured times of ~41000 launch
 // configurations (every shape the candidate loops below produce) of the 13
 // VGG-16 layers at 32 px (batch 128, fp32), four of its layers at 224 px
 // (batch 128), the 256->256 14x14 layer at 50..99 % sparsity (batch 256) and six
@@ -83,16 +84,16 @@ void rows_per_wavefront(int nrows, int WP, int WK, int KW, std::vector<int>& roo
 // the best measured one and its time within ~10 % of the measured.
 //  * A step (kBatch stored weights of one output channel, for the 64 * LP positions
 //    of a wavefront) costs its SIMD kBatch * LP * V multiply-adds of ~4 clocks
-//    (fp16: the mixed-precision multiply-add takes ~4.4) plus ~8 clocks a weight
-//    for the address and loop control, and the CU's LDS kBatch * LP * 64 elements
+//    (fp16: the mixed-precision multiply-add takes ~4.4) plus ~4 clocks a weight
+//    for the address, and the CU's LDS kBatch * LP * 64 elements
 //    at ~225 B/clk.  For 16-byte fp32 elements the two are about equal, and they
 //    overlap for the most part.
-//  * The multiply-adds that count are those of the SIMD with the most rows (see
+//  * A SIMD's multiply-adds are those of the rows its wavefronts hold (see
 //    rows_per_wavefront); the LDS reads are the whole CU's.
 //  * A lone wavefront cannot hide its own LDS and scalar-fetch latency (~170 clocks a step).
 //  * Registers (56 + accumulators + two groups of LDS reads in flight) bound the
 //    wavefronts resident on a SIMD, and with them the workgroups on a CU.
-//  * Staging moves ~24 B/clk/CU from L2 and overlaps the arithmetic except for the
+//  * Staging moves ~16 B/clk/CU from L2 and overlaps the arithmetic except for the
 //    first chunk; a workgroup costs ~7 us to start and finish, a chunk ~0.4 us.
 //  * Workgroups run in rounds of (CUs * resident workgroups); a partly filled
 //    last round still takes a round.
@@ -100,7 +101,7 @@ double estimate(const Shape& s, const Cand& c)
 {
     const int nchunks = cdiv(s.C, c.Cc);
     const double seg = s.row_nnz * c.Cc / s.C;
-    const double batches = nchunks == 1 ? std::ceil(seg / kBatch) : seg / kBatch + 1.0;
+    const double batches = nchunks == 1 ? std::ceil(seg / kBatch) : seg / kBatch + 0.8;
     const int waves = c.WP * c.WK;
     const double regs = std::min(128.0, 56.0 + c.KW * c.LP * c.V + 4.0 * c.LP * (s.ub / 4.0));  // the kernels are built for <= 128
     const int per_simd = std::min(8, 512 / (8 * (int)std::ceil(regs / 8.0)));
@@ -111,19 +112,16 @@ double estimate(const Shape& s, const Cand& c)
     // rows on the fullest SIMD and wavefront-rows in all of a typical channel block
     std::vector<int> room;
     rows_per_wavefront(cdiv(s.K, kblocks), c.WP, c.WK, c.KW, room);
-    long long rows_on[4] = {0, 0, 0, 0}, rows_all = 0;
-    for (int w = 0; w < c.WK; ++w)
-        for (int q = 0; q < c.WP; ++q) {
-            rows_on[(w * c.WP + q) & 3] += room[w];
-            rows_all += room[w];
-        }
-    const double rows_max = (double)std::max(std::max(rows_on[0], rows_on[1]), std::max(rows_on[2], rows_on[3]));
+    long long rows_all = 0;
+    for (int w = 0; w < c.WK; ++w) rows_all += (long long)room[w] * c.WP;
+    // with the empty slots spread as they are the SIMDs differ by a row at most: the mean fits as well as the maximum
+    const double rows_simd = (double)rows_all / 4.0;
     const double fma_clk = s.elem_bytes == 2 ? 4.4 : 4.0;
-    const double v_step = kBatch * (c.LP * c.V * fma_clk + 8.0);
+    const double v_step = kBatch * (c.LP * c.V * fma_clk + 4.0);
     const double l_step = kBatch * c.LP * 64.0 * s.ub / 225.0;
     const double gbytes = (double)s.C * c.CS * s.ub * ((double)s.W / s.Wp) * std::min(1.0, (double)s.H / s.Hs);
     const double fixed = 16000.0 + 1000.0 * nchunks;
-    const double one_row_only = c.KW == 1 ? 1.2 : 1.0;   // measured residual
+    const double shape_factor = c.KW == 1 ? 1.2 : c.KW == 8 ? 1.05 : 1.0;   // measured residuals
     double t = 0.0;
     long long remaining = wgs;
     const long long slots = (long long)kCUs * conc_max;
@@ -131,11 +129,11 @@ double estimate(const Shape& s, const Cand& c)
         const long long n = std::min(remaining, slots);
         const int conc = (int)((n + kCUs - 1) / kCUs);
         // one batch of every row of the resident workgroups: the fullest SIMD's multiply-adds, the CU's LDS reads
-        const double a = conc * rows_max * v_step, b = conc * (double)rows_all * l_step;
-        const double shared = std::max(a, b) + 0.3 * std::min(a, b);
+        const double a = conc * rows_simd * v_step, b = conc * (double)rows_all * l_step;
+        const double shared = (std::max(a, b) + 0.3 * std::min(a, b)) / 0.92;
         const double per_batch = std::max(shared, c.KW * (v_step + 170.0));
-        const double t_compute = batches * nchunks * one_row_only * per_batch;
-        const double t_stage = conc * gbytes / 24.0;
+        const double t_compute = batches * nchunks * shape_factor * per_batch;
+        const double t_stage = conc * gbytes / 16.0;
         const long long full = remaining / slots;
         const double round = std::max(t_compute, t_stage) + t_stage / nchunks + fixed;
         if (full > 1) {            // identical full rounds
