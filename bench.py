@@ -62,7 +62,7 @@ def layer_roofs(run, N, b):
 
 
 # mean HBM-side bytes per launch of sc::tile_kernel (see profiles/)
-MEASURED_TRAFFIC = {"vgg16_f32": 27.1e6, "vgg16_f16": 27.7e6}
+MEASURED_TRAFFIC = {"vgg16_f32": 27.3e6, "vgg16_f16": 28.4e6}
 
 
 def cpu_baseline(net, work, budget_s=12.0):
@@ -110,6 +110,9 @@ def main():
     ap.add_argument("--compare-dense", action="store_true",
                     help="also time the platform's dense convolution (torch / MIOpen) per layer and report which "
                          "of the two a dispatcher would pick")
+    ap.add_argument("--buffer-mib", type=int, default=512,
+                    help="the timed steps go round copies of the resident activations that together hold at least "
+                         "this much (at most 16 copies), so that the last-level cache cannot serve them; 0: one set")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="after the timed steps, copy a device buffer of this size once (a kernel of known "
                          "traffic that calibrates rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
@@ -134,28 +137,37 @@ def main():
     if args.autotune > 0 and not args.launch:
         net.autotune(args.autotune)
 
-    for _ in range(args.warmup):
-        net.step()
-    torch.cuda.synchronize()
-    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    t0 = time.perf_counter()
-    ev0.record()
-    for _ in range(args.steps):
-        net.step()
-    ev1.record()
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-    gpu_ms = ev0.elapsed_time(ev1)
+    # Buffer sets: the timed steps go round copies of the resident activations that together exceed
+    # the last-level cache (256 MB), so that no step finds its operands left there by the one before;
+    # the same loop on a single set is reported beside it as the cache-hot figure.
+    nsets = net.make_buffer_sets(args.buffer_mib << 20) if args.buffer_mib > 0 else 1
+
+    def timed(rotate):
+        for i in range(args.warmup):
+            net.step(i if rotate else 0)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        e0.record()
+        for i in range(args.steps):
+            net.step(i if rotate else 0)
+        e1.record()
+        torch.cuda.synchronize()
+        return time.perf_counter() - t0, e0.elapsed_time(e1)
+
+    hot_wall, _ = timed(False)
+    wall, gpu_ms = timed(True)
     ms_per_step = wall * 1e3 / args.steps
 
     # per-layer durations, in the order and cache state of a step: events between the launches of
     # further (untimed) steps on the launch stream
     reps = max(10, min(args.steps, 50))
     marks = [[torch.cuda.Event(enable_timing=True) for _ in range(len(net.runs) + 1)] for _ in range(reps)]
-    for ev in marks:
+    for j, ev in enumerate(marks):
         ev[0].record()
         for i, r in enumerate(net.runs):
-            r.layer.forward(r.x, r.spec.stride, r.spec.pad, out=r.y)
+            x, y = net.sets[j % nsets][i] if nsets > 1 else (r.x, r.y)
+            r.layer.forward(x, r.spec.stride, r.spec.pad, out=y)
             ev[i + 1].record()
     torch.cuda.synchronize()
     layers = []
@@ -212,9 +224,10 @@ def main():
         "unit": "GFLOP/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "gpu_ms_per_step": gpu_ms / args.steps,
+        "cache_hot_ms_per_step": hot_wall * 1e3 / args.steps, "buffer_sets": nsets,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": work.dtype, "data": "synthetic",
-        "config": {"workload": f"{work.name}, batch {N}, {nl} sparse conv layer(s), conv only, inputs resident in HBM",
+        "config": {"workload": f"{work.name}, batch {N}, {nl} sparse conv layer(s), conv only, inputs resident in HBM, {nsets} buffer set(s) in rotation",
                    "layers": nl, "batch": N, "total_macs": total_macs,
                    "launch": (f"override {args.launch}" if args.launch else
                               f"measured best of {args.autotune} ranked candidates per layer" if args.autotune > 0

@@ -77,10 +77,26 @@ class Network:
         return [run.layer.autotune(run.x, run.spec.stride, run.spec.pad, out=run.y, max_candidates=max_candidates)
                 for run in self.runs]
 
-    def step(self):
-        """One pass of the hot path: every layer's convolution on its resident input."""
-        for run in self.runs:
-            run.layer.forward(run.x, run.spec.stride, run.spec.pad, out=run.y)
+    def make_buffer_sets(self, min_bytes: int = 512 << 20, max_sets: int = 16) -> int:
+        """Further copies of every layer's resident input (and outputs of their own) at other
+        addresses, until all sets together hold min_bytes: passes that go round the sets do not
+        find their operands in the 256 MB last-level cache.  Returns the number of sets."""
+        import torch
+        per_set = sum(r.x.numel() * r.x.element_size() + r.y.numel() * r.y.element_size() for r in self.runs)
+        nsets = max(1, min(max_sets, -(-min_bytes // per_set)))
+        self.sets = [[(r.x, r.y) for r in self.runs]]
+        for _ in range(nsets - 1):
+            self.sets.append([(r.x.clone(), torch.empty_like(r.y)) for r in self.runs])
+        torch.cuda.synchronize()
+        return nsets
+
+    def step(self, which: int = 0):
+        """One pass of the hot path: every layer's convolution on its resident input
+        (buffer set `which`, modulo the number of sets, once make_buffer_sets has run)."""
+        sets = getattr(self, "sets", None)
+        bufs = sets[which % len(sets)] if sets else [(r.x, r.y) for r in self.runs]
+        for run, (x, y) in zip(self.runs, bufs):
+            run.layer.forward(x, run.spec.stride, run.spec.pad, out=y)
 
     def compare_with_dense(self, reps: int = 20):
         """Per layer: time of the sparse kernel and of the platform's dense convolution

@@ -198,6 +198,28 @@ def test_dense_comparison_routes_every_layer():
     net.close()
 
 
+def test_buffer_sets_in_rotation_give_the_same_outputs():
+    """The copies of the activations that the timed steps of bench.py go round hold the same
+    inputs at other addresses; a pass over any of them leaves the same outputs as the first."""
+    import torch
+    from paper_2011_06295_amd import workloads as wl
+    work = wl.vgg16(8, "f32")
+    net = _net(work)
+    net.run_chain(wl.make_input(work))
+    first = [r.y.clone() for r in net.runs]
+    nsets = net.make_buffer_sets(3 * sum(r.x.numel() * 4 + r.y.numel() * 4 for r in net.runs))
+    assert nsets == 3 and len(net.sets) == 3
+    for which in (1, 2, 3):
+        for _, y in net.sets[which % 3]:
+            y.fill_(float("nan"))
+        net.step(which)
+        torch.cuda.synchronize()
+        for li, (x, y) in enumerate(net.sets[which % 3]):
+            assert which % 3 == 0 or x.data_ptr() != net.runs[li].x.data_ptr()
+            assert torch.equal(y, first[li]), (which, li)
+    net.close()
+
+
 def test_config5_unify_flag_matches_plain_rows():
     """Ragged rows padded to a unified count with explicit zeros give the same numbers."""
     import torch
