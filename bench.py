@@ -209,6 +209,11 @@ def main():
         roofline = {"bound": "hbm", "achieved": sums["hbm_bytes"] / nl / avg_launch_s / 1e9, "peak": HBM_PEAK / 1e9,
                     "unit": "GB/s"}
     roofline["frac"] = roofline["achieved"] / roofline["peak"]
+    if roofline["bound"] == "lds":
+        # beside the nominal figure: the ds_read_b128 rate a bare read loop reaches on this chip (225 B/clk/CU),
+        # and the rate of the bare inner loop's own mix of reads and multiply-adds (0.56 of nominal)
+        roofline["frac_of_measured_read_rate"] = roofline["achieved"] / (256 * 225 * 2.4)
+        roofline["frac_of_inner_loop_ceiling"] = roofline["frac"] / 0.56
     # HBM-side bytes per launch, measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE and scaled by a copy
     # of known size (profiles/tile_kernel_*_hbm_traffic.md); null for workloads that were not profiled
     roofline["traffic"] = MEASURED_TRAFFIC.get(args.workload)

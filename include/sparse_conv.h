@@ -14,6 +14,10 @@
  *     device memory of the current device (for instance tensor.data_ptr() of a
  *     PyTorch-ROCm tensor); the library never takes ownership of either;
  *   - all arrays are dense, contiguous, row-major in the index order written;
+ *   - a handle keeps its device tables on the device that was current at the
+ *     first call that needed them (sparse_conv_forward, sparse_conv_autotune,
+ *     sparse_conv_set_epilogue with a bias); later such calls with another
+ *     device current return SC_EINVAL;
  *   - the handle is not thread-safe against concurrent calls on itself.
  */
 #ifndef SPARSE_CONV_H
@@ -90,6 +94,11 @@ int sparse_conv_output_shape(sparse_conv_t h, int H, int W, int stride, int pad,
  * and uploads a per-geometry plan (one synchronous allocation + copy);
  * further calls with the same geometry allocate nothing and enqueue exactly one
  * kernel, so they may be recorded into a HIP graph on a capturing stream.
+ * Limits: input and output below 2^31 elements each (SC_EUNSUPPORTED beyond).
+ * Non-finite input values: an output that the definition makes +-Inf may come
+ * out as NaN (the stored rows are padded to multiples of four taps by repeating
+ * a row's last tap with weight zero, and 0 * Inf is NaN); finite inputs are
+ * not affected, the padding terms are exact zeros.
  */
 int sparse_conv_forward(sparse_conv_t h, const void* input, void* output,
                         int N, int H, int W, int stride, int pad, void* stream);

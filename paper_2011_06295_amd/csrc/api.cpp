@@ -55,23 +55,40 @@ int get_plan(sparse_conv_s* h, const Geometry& g, Plan** out)
     return SC_OK;
 }
 
+// A handle's device buffers (plan tables, bias) live on the device that was current when the
+// first of them was made; calls with another device current are refused.
+int bind_device(sparse_conv_s* h)
+{
+    int dev = -1;
+    const hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) {
+        h->last_hip = (int)e;
+        return SC_EHIP;
+    }
+    if (h->device < 0) h->device = dev;
+    return h->device == dev ? SC_OK : SC_EINVAL;
+}
+
 template <typename T>
 int upload(sparse_conv_s* h, const std::vector<T>& v, void** dst)
 {
+    if (*dst) return SC_OK;   // already there (an earlier call got this far before it failed)
     const size_t bytes = std::max<size_t>(v.size(), 1) * sizeof(T);
-    hipError_t e = hipMalloc(dst, bytes);
+    void* d = nullptr;
+    hipError_t e = hipMalloc(&d, bytes);
     if (e != hipSuccess) {
         h->last_hip = (int)e;
-        *dst = nullptr;
         return e == hipErrorOutOfMemory ? SC_ENOMEM : SC_EHIP;
     }
     if (!v.empty()) {
-        e = hipMemcpy(*dst, v.data(), v.size() * sizeof(T), hipMemcpyHostToDevice);
+        e = hipMemcpy(d, v.data(), v.size() * sizeof(T), hipMemcpyHostToDevice);
         if (e != hipSuccess) {
             h->last_hip = (int)e;
+            (void)hipFree(d);
             return SC_EHIP;
         }
     }
+    *dst = d;
     return SC_OK;
 }
 
@@ -187,6 +204,8 @@ int sparse_conv_set_epilogue(sparse_conv_t h, const float* bias, unsigned flags)
     if (!h || (flags & ~static_cast<unsigned>(SC_EPILOGUE_RELU))) return SC_EINVAL;
     float* d = nullptr;
     if (bias) {
+        const int rc = sc::bind_device(h);
+        if (rc != SC_OK) return rc;
         hipError_t e = hipMalloc(reinterpret_cast<void**>(&d), sizeof(float) * (size_t)h->K);
         if (e == hipSuccess) e = hipMemcpy(d, bias, sizeof(float) * (size_t)h->K, hipMemcpyHostToDevice);
         if (e != hipSuccess) {
@@ -232,6 +251,7 @@ int sparse_conv_forward(sparse_conv_t h, const void* input, void* output,
         // the kernels index both tensors with 32-bit element offsets
         if ((long long)N * h->C * H * W >= (1ll << 31) || (long long)N * h->K * p->E * p->F >= (1ll << 31))
             return SC_EUNSUPPORTED;
+        if ((rc = sc::bind_device(h)) != SC_OK) return rc;
         if (!p->uploaded) {
             if ((rc = sc::upload(h, p->entries, &p->d_entries)) != SC_OK) return rc;
             if ((rc = sc::upload(h, p->seg, &p->d_seg)) != SC_OK) return rc;

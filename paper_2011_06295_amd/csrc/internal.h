@@ -177,4 +177,5 @@ struct sparse_conv_s {
     std::map<sc::Geometry, sc::Launch> tuned;   // per geometry: configuration found by sparse_conv_autotune
     std::map<sc::Geometry, std::unique_ptr<sc::Plan>> plans;
     int last_hip = 0;
+    int device = -1;           // HIP device that holds the handle's device buffers; -1 until the first is made
 };
