@@ -41,3 +41,13 @@ def test_generators_are_deterministic():
     x = wl.make_input(wl.lenet5())
     assert x.shape == (64, 1, 28, 28) and x.min() >= 0 and x.max() < 1
     assert np.array_equal(x, wl.make_input(wl.lenet5()))
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py is a one-GPU benchmark: any other --gpus value ends with a message, before touching a GPU."""
+    import os, subprocess, sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"],
+                       capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "one GPU" in (r.stderr + r.stdout)
