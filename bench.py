@@ -134,7 +134,9 @@ def main():
     net.run_chain(wl.make_input(work))
     N = work.N
     b = 2 if work.dtype == "f16" else 4
-    if args.autotune > 0 and not args.launch:
+    pinned = [int(v) for v in args.launch.split(",")] if args.launch else []
+    tune = args.autotune > 0 and not all(pinned[:4] + [len(pinned) >= 4])   # a launch shape given in full is taken as it is
+    if tune:
         net.autotune(args.autotune)
 
     # Buffer sets: the timed steps go round copies of the resident activations that together exceed
@@ -181,7 +183,7 @@ def main():
             "bound": bound[0], "roof_frac": round(bound[1] / t, 4),
             "hbm_GBs": round(roofs["hbm_bytes"] / t / 1e9, 1), "lds_GBs": round(roofs["lds_bytes"] / t / 1e9, 1),
             "launch": {k: v for k, v in r.layer.get_launch(N, r.spec.H, r.spec.W, r.spec.stride, r.spec.pad).items()
-                       if k in ("V", "WP", "WK", "KW", "Cc", "LP", "kblocks", "grid", "lds_bytes", "threads")},
+                       if k in ("V", "WP", "WK", "KW", "Cc", "LP", "kblocks", "store", "grid", "lds_bytes", "threads")},
         })
 
     if args.copy_probe_mib > 0:
@@ -234,9 +236,9 @@ def main():
         "dtype": work.dtype, "data": "synthetic",
         "config": {"workload": f"{work.name}, batch {N}, {nl} sparse conv layer(s), conv only, inputs resident in HBM, {nsets} buffer set(s) in rotation",
                    "layers": nl, "batch": N, "total_macs": total_macs,
-                   "launch": (f"override {args.launch}" if args.launch else
-                              f"measured best of {args.autotune} ranked candidates per layer" if args.autotune > 0
-                              else "cost estimate")},
+                   "launch": ((f"override {args.launch}; " if args.launch else "") +
+                              (f"measured best of {args.autotune} ranked candidates per layer" if tune
+                               else "cost estimate"))},
         "roofline": roofline,
         "layers": layers,
     }

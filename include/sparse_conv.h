@@ -154,6 +154,10 @@ int sparse_conv_get_codebook(sparse_conv_t h, const unsigned char** codes, const
  *   [7] channel blocks the K output channels are dealt over (a workgroup takes one
  *           block; at least ceil(K / (WK * KW)), more leaves row slots empty on the
  *           wavefronts a SIMD serves last; fewer is SC_EUNSUPPORTED)
+ *   [8] output stores: 1 ordinary, 2 non-temporal (the output bypasses the cache
+ *           lines the other workgroups of the launch still read their input from;
+ *           faster for some layers, slower for others: sparse_conv_autotune
+ *           measures both); automatic without a measurement is 1
  * Missing trailing entries and zeros mean "automatic".  nparams = 0 restores
  * the automatic choice.  Cached plans are discarded.  SC_EINVAL for values the
  * kernels cannot run; a configuration that cannot fit is reported by forward.
@@ -165,8 +169,9 @@ int sparse_conv_set_launch(sparse_conv_t h, const int* params, int nparams);
  * measurement (section 8 sets the thread-block count of each layer by
  * experiment; section 9 reports what an untuned choice costs).  Runs the layer on the given buffers with the max_candidates
  * (<= 0: 8) configurations the cost estimate ranks best, within whatever
- * sparse_conv_set_launch has pinned, times each with events on `stream`, and
- * keeps the fastest for later forwards of this (N,H,W,stride,pad).
+ * sparse_conv_set_launch has pinned, times each with events on `stream`, times
+ * the three fastest once more with the other kind of output store, and keeps the
+ * fastest for later forwards of this (N,H,W,stride,pad).
  *   input, output, N..pad, stream   as for sparse_conv_forward (N > 0); output is
  *            overwritten with the layer's result.
  *   best_us  if not NULL receives the kept configuration's time per launch, in us.
@@ -194,9 +199,9 @@ int sparse_conv_set_epilogue(sparse_conv_t h, const float* bias, unsigned flags)
 /* The launch configuration chosen for a geometry: [0] V .. [4] Cc, [5] the LDS
  * budget in force, [6] workgroups launched, [7] LDS bytes
  * per workgroup, [8] threads per workgroup, [9] stored plan entries
- * (including batch padding), [10] LP, [11] channel blocks.  [0..5] are in the order of
- * sparse_conv_set_launch.  Builds the plan's host side if needed; needs no
- * GPU.  params must have room for 12 ints. */
+ * (including batch padding), [10] LP, [11] channel blocks, [12] kind of output store
+ * (1 or 2).  [0..5] are in the order of sparse_conv_set_launch.  Builds the plan's
+ * host side if needed; needs no GPU.  params must have room for 13 ints. */
 int sparse_conv_get_launch(sparse_conv_t h, int N, int H, int W, int stride, int pad, int* params);
 
 /* HIP error code of the last failing runtime call made through this handle (0 if none). */

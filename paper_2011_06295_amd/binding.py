@@ -180,9 +180,9 @@ def sparse_conv_autotune(handle: int, input_ptr: int, output_ptr: int, N: int, H
 
 
 def sparse_conv_get_launch(handle: int, N: int, H: int, W: int, stride: int, pad: int) -> dict:
-    arr = (C.c_int * 12)()
+    arr = (C.c_int * 13)()
     _check(_lib.sparse_conv_get_launch(handle, N, H, W, stride, pad, arr), "sparse_conv_get_launch", handle)
-    names = ("V", "WP", "WK", "KW", "Cc", "lds_budget", "grid", "lds_bytes", "threads", "entries", "LP", "kblocks")
+    names = ("V", "WP", "WK", "KW", "Cc", "lds_budget", "grid", "lds_bytes", "threads", "entries", "LP", "kblocks", "store")
     return dict(zip(names, list(arr)))
 
 

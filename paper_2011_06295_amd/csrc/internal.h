@@ -52,6 +52,7 @@ struct Launch {
     int lds_budget = 0;
     int LP = 0;   // positions per lane (1 or 2)
     int kblocks = 0;  // channel blocks (at least ceil(K / (WK * KW)); more leaves slots empty)
+    int store = 0;    // output stores: 1 ordinary, 2 non-temporal (the output is not read again by this kernel)
 };
 
 struct Geometry {
@@ -86,6 +87,7 @@ struct Entry {
 // read neighbouring LDS elements, whatever the tap.
 struct Plan {
     int V, WP, WK, KW, Cc, LP;
+    int store;     // 1 ordinary output stores, 2 non-temporal
     int E, F;
     int Wp;        // row pitch of the padded lattice
     int Hs;        // rows per image group
@@ -141,6 +143,7 @@ struct KernelArgs {
     const int* krow;
     const float* bias;   // [K] or null
     int relu;            // clamp the stored value at zero
+    int nt_store;        // non-temporal output stores
     int N, C, H, W, K, E, F, stride, pad;
     int WP, WK, Cc, Wp, Hs, Hb, CS, span;
     int nchunks, ngroups, ntiles, kblocks;

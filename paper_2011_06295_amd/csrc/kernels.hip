@@ -67,6 +67,20 @@ __device__ __forceinline__ _Float16 load_elem<_Float16>(__amdgpu_buffer_rsrc_t r
     return r;
 }
 
+// One output element stored with the non-temporal hint.  Written as an instruction of its
+// own: a hinted and a plain store under a run-time switch would be merged into one plain store.
+__device__ __forceinline__ void store_nontemporal(float* p, float v)
+{
+    asm volatile("global_store_dword %0, %1, off nt" ::"v"(p), "v"(v) : "memory");
+}
+__device__ __forceinline__ void store_nontemporal(_Float16* p, _Float16 v)
+{
+    unsigned short h;
+    __builtin_memcpy(&h, &v, 2);
+    const unsigned bits = h;
+    asm volatile("global_store_short %0, %1, off nt" ::"v"(p), "v"(bits) : "memory");
+}
+
 template <typename T, int V>
 struct Vec {
     typedef T type __attribute__((ext_vector_type(V)));
@@ -501,7 +515,12 @@ __global__ __launch_bounds__(1024) void tile_kernel(const KernelArgs a)
                 const int n = g * V + v;
                 float r = acc[kk][p][v] + bias;
                 if (a.relu) r = r > 0.f ? r : 0.f;
-                if (n < a.N) y[((size_t)n * a.K + k) * plane + pix] = (T)r;
+                if (n >= a.N) continue;
+                T* at = &y[((size_t)n * a.K + k) * plane + pix];
+                if (a.nt_store)
+                    store_nontemporal(at, (T)r);
+                else
+                    *at = (T)r;
             }
         }
     }

@@ -176,6 +176,7 @@ int build_plan(const Csr& csr, int C, int R, int S, int elem_bytes, const Geomet
     const int vmax = 16 / elem_bytes;
     if (over.V && !pow2_in(over.V, 1, vmax)) return SC_EINVAL;
     if (over.LP && !pow2_in(over.LP, 1, 2)) return SC_EINVAL;
+    if (over.store < 0 || over.store > 2) return SC_EINVAL;
 
     // ---- candidates
     static const int budgets[] = {160 * 1024, 80 * 1024, 53 * 1024, 40 * 1024, 32 * 1024};
@@ -276,6 +277,7 @@ int build_plan(const Csr& csr, int C, int R, int S, int elem_bytes, const Geomet
                             if (ranked) {
                                 Launch l;
                                 l.V = V; l.WP = wp; l.WK = wk; l.KW = kw; l.Cc = Cc; l.LP = LP; l.kblocks = kblocks;
+                                l.store = over.store;
                                 ranked->emplace_back(t, l);
                             }
                             if (best_t < 0 || t < best_t) {
@@ -311,6 +313,7 @@ int build_plan(const Csr& csr, int C, int R, int S, int elem_bytes, const Geomet
     const int V = best.V;
     const int ngroups = std::max(1, cdiv(g.N, V));
     p.V = V; p.WP = best.WP; p.WK = best.WK; p.KW = best.KW; p.Cc = best.Cc; p.LP = best.LP;
+    p.store = over.store ? over.store : 1;   // which kind is faster depends on what else lives in L2: only a measurement tells
     p.Wp = s.Wp; p.Hs = s.Hs;
     p.span = kWave * p.WP * p.LP;
     p.Hb = best.Hb; p.CS = best.CS;

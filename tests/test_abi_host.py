@@ -95,7 +95,11 @@ def test_argument_validation_returns_status_codes():
     assert lib.sparse_conv_set_launch(h, bad, 6) == B.SC_EINVAL                                  # V must be a power of two
     lp3 = (C.c_int * 7)(0, 0, 0, 0, 0, 0, 3)
     assert lib.sparse_conv_set_launch(h, lp3, 7) == B.SC_EINVAL                                  # positions per lane: 1 or 2
-    assert lib.sparse_conv_set_launch(h, lp3, 9) == B.SC_EINVAL                                  # at most 8 parameters
+    assert lib.sparse_conv_set_launch(h, lp3, 10) == B.SC_EINVAL                                 # at most 9 parameters
+    st3 = (C.c_int * 9)(0, 0, 0, 0, 0, 0, 0, 0, 3)
+    assert lib.sparse_conv_set_launch(h, st3, 9) == B.SC_EINVAL                                  # kind of output store: 1 or 2
+    st3[8] = 2
+    assert lib.sparse_conv_set_launch(h, st3, 9) == B.SC_OK
     lp3[6] = 2
     assert lib.sparse_conv_set_launch(h, lp3, 7) == B.SC_OK
     assert lib.sparse_conv_set_launch(h, None, 0) == B.SC_OK
@@ -181,7 +185,7 @@ def test_sizes_beyond_the_kernels_index_range_are_refused():
     w = np.ones((2, 1, 3, 3), np.float32)
     m = np.ones((2, 1, 3, 3), np.uint8)
     layer = B.SparseConv(w, m)
-    out = (C.c_int * 12)()
+    out = (C.c_int * 13)()
     # 2^22 images of 64x64: more than 2^31 lattice positions whatever the interleave
     assert lib.sparse_conv_get_launch(layer.handle, 1 << 22, 64, 64, 1, 1, out) == B.SC_EUNSUPPORTED
     # 70000 images of 181x181: the lattice fits, the input tensor has more than 2^31 elements;

@@ -88,6 +88,8 @@ LAUNCHES = [
     [0, 2, 2, 2, 0, 0, 2],
     [4, 1, 3, 4, 0, 0, 1, 5],     # 37 output channels over 5 blocks of 12 slots: 4-5 empty slots a block
     [0, 1, 4, 2, 6, 0, 1, 37],    # one output channel per workgroup
+    [4, 2, 2, 4, 0, 0, 1, 0, 2],  # non-temporal output stores
+    [0, 0, 0, 0, 0, 0, 2, 0, 2],
 ]
 
 
@@ -192,10 +194,12 @@ def test_measured_launch_choice_keeps_the_result(dtype):
     tuned = layer.get_launch(N, H, W, 1, 1)
     other = layer.get_launch(N + 1, H, W, 1, 1)          # another geometry keeps the estimate's choice
     assert 64 <= tuned["threads"] <= 1024 and other["threads"] >= 64
+    assert tuned["store"] in (1, 2) and other["store"] == 1
     after = run_gpu(layer, x, 1, 1, dtype)
     assert_close(after, ref, TOL[dtype], f"autotuned-{dtype}")
     assert_close(before, ref, TOL[dtype], f"estimated-{dtype}")
-    layer.set_launch([tuned["V"], tuned["WP"], tuned["WK"], tuned["KW"], tuned["Cc"], 0, tuned["LP"], tuned["kblocks"]])   # pinning it by hand gives the same plan
+    layer.set_launch([tuned["V"], tuned["WP"], tuned["WK"], tuned["KW"], tuned["Cc"], 0, tuned["LP"], tuned["kblocks"],
+                      tuned["store"]])   # pinning it by hand gives the same plan
     pinned = layer.get_launch(N, H, W, 1, 1)
     assert pinned == tuned
     layer.close()
