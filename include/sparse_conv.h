@@ -196,6 +196,15 @@ int sparse_conv_autotune(sparse_conv_t h, const void* input, void* output,
  */
 int sparse_conv_set_epilogue(sparse_conv_t h, const float* bias, unsigned flags);
 
+/* Diagnostic: builds (or takes the cached) plan of a geometry and checks it on the
+ * host against the CSR: every stored weight appears exactly once, with the LDS
+ * offset of its tap (section 7's pre-computed input offsets) inside the staged
+ * tile, every output channel has one accumulator slot, the tables have the sizes
+ * the kernel walks, and the launch fits the hardware.  *failed_check receives 0,
+ * or the number of the first check that failed.  Needs no GPU.  Returns SC_OK
+ * when the check ran (whatever it found), else as sparse_conv_get_launch. */
+int sparse_conv_check_plan(sparse_conv_t h, int N, int H, int W, int stride, int pad, int* failed_check);
+
 /* The launch configuration chosen for a geometry: [0] V .. [4] Cc, [5] the LDS
  * budget in force, [6] workgroups launched, [7] LDS bytes
  * per workgroup, [8] threads per workgroup, [9] stored plan entries

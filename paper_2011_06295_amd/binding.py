@@ -25,7 +25,7 @@ LIB_PATH = os.environ.get("SPARSECONV_LIBRARY") or os.path.join(
 EXPORTS = (
     "sparse_conv_create", "sparse_conv_output_shape", "sparse_conv_forward",
     "sparse_conv_get_csr", "sparse_conv_set_launch", "sparse_conv_get_launch", "sparse_conv_set_epilogue", "sparse_conv_autotune",
-    "sparse_conv_create_codebook", "sparse_conv_get_codebook",
+    "sparse_conv_create_codebook", "sparse_conv_get_codebook", "sparse_conv_check_plan",
     "sparse_conv_last_hip_error", "sparse_conv_strerror", "sparse_conv_destroy",
 )
 
@@ -59,6 +59,7 @@ def _load():
     lib.sparse_conv_set_launch.argtypes = [vp, ip, C.c_int]
     lib.sparse_conv_get_launch.argtypes = [vp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, ip]
     lib.sparse_conv_set_epilogue.argtypes = [vp, vp, C.c_uint]
+    lib.sparse_conv_check_plan.argtypes = [vp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, ip]
     lib.sparse_conv_autotune.argtypes = [vp, vp, vp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, vp, C.c_int,
                                          C.POINTER(C.c_float)]
     lib.sparse_conv_last_hip_error.argtypes = [vp]
@@ -186,6 +187,13 @@ def sparse_conv_get_launch(handle: int, N: int, H: int, W: int, stride: int, pad
     return dict(zip(names, list(arr)))
 
 
+def sparse_conv_check_plan(handle: int, N: int, H: int, W: int, stride: int, pad: int) -> int:
+    """Host-side consistency check of the geometry's plan: 0, or the number of the first failed check."""
+    bad = C.c_int(-1)
+    _check(_lib.sparse_conv_check_plan(handle, N, H, W, stride, pad, C.byref(bad)), "sparse_conv_check_plan", handle)
+    return int(bad.value)
+
+
 def sparse_conv_destroy(handle: Optional[int]) -> None:
     _lib.sparse_conv_destroy(handle)
 
@@ -223,6 +231,9 @@ class SparseConv:
 
     def output_shape(self, H: int, W: int, stride: int = 1, pad: int = 0):
         return sparse_conv_output_shape(self.handle, H, W, stride, pad)
+
+    def check_plan(self, N: int, H: int, W: int, stride: int = 1, pad: int = 0) -> int:
+        return sparse_conv_check_plan(self.handle, N, H, W, stride, pad)
 
     def set_launch(self, params: Sequence[int]):
         sparse_conv_set_launch(self.handle, params)

@@ -399,6 +399,22 @@ int sparse_conv_autotune(sparse_conv_t h, const void* input, void* output,
     }
 }
 
+int sparse_conv_check_plan(sparse_conv_t h, int N, int H, int W, int stride, int pad, int* failed_check)
+{
+    if (!h || N < 0) return SC_EINVAL;
+    if (!sc::geometry_ok(h, H, W, stride, pad)) return SC_EINVAL;
+    try {
+        sc::Plan* p = nullptr;
+        int rc = sc::get_plan(h, sc::Geometry{N, H, W, stride, pad}, &p);
+        if (rc != SC_OK) return rc;
+        const int bad = sc::check_plan(h->csr, h->C, h->R, h->S, h->dtype == SC_F16 ? 2 : 4, *p);
+        if (failed_check) *failed_check = bad;
+        return SC_OK;
+    } catch (...) {
+        return SC_ENOMEM;
+    }
+}
+
 int sparse_conv_last_hip_error(sparse_conv_t h) { return h ? h->last_hip : 0; }
 
 const char* sparse_conv_strerror(int code)

@@ -127,6 +127,11 @@ struct Plan {
 int build_plan(const Csr& csr, int C, int R, int S, int elem_bytes, const Geometry& g,
                const Launch& over, Plan& plan, std::vector<std::pair<double, Launch>>* ranked = nullptr);
 
+// Checks a built plan against its CSR on the host (every stored weight exactly once, with its
+// tap's LDS offset, inside the tile; every output channel in one slot; table sizes; launch
+// limits).  Returns 0, or the number of the first failed check.
+int check_plan(const Csr& csr, int C, int R, int S, int elem_bytes, const Plan& plan);
+
 // ---------------------------------------------------------------- kernels
 
 // Division by a run-time constant: q = n / d for 0 <= n < 2^31.

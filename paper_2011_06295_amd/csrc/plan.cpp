@@ -439,4 +439,79 @@ int build_plan(const Csr& csr, int C, int R, int S, int elem_bytes, const Geomet
     return SC_OK;
 }
 
+// Host-side consistency check of a built plan against the CSR it was made from.
+// 0 = consistent; otherwise the number of the first check that failed.
+int check_plan(const Csr& csr, int C, int R, int S, int elem_bytes, const Plan& p)
+{
+    const int K = csr.K, RS = R * S;
+    const int ub = p.V * elem_bytes;
+    const int KB = p.WK * p.KW, SW = p.KW + 1;
+    // 1: launch shape within the hardware's limits
+    if (p.threads != kWave * p.WP * p.WK || p.threads > kWave * kMaxWaves || p.lds_bytes > kMaxLds) return 1;
+    if (p.nchunks != cdiv(C, p.Cc) || (p.nbuf != 1 && p.nbuf != 2) || (p.nchunks > 1 && p.nbuf != 2)) return 1;
+    if ((long long)p.tbl_off + (long long)p.SL * 8 > p.lds_bytes) return 1;
+    if (((long long)p.nbuf * p.Cc * p.CS + 1) * ub > p.tbl_off) return 1;
+    if ((long long)p.grid < (long long)p.ntiles * p.kblocks || p.grid % 8 != 0) return 1;
+    if ((long long)p.ntiles * p.span < p.npos || (long long)(p.ntiles - 1) * p.span >= p.npos) return 1;
+    // 2: every output channel owns exactly one accumulator slot
+    if (p.krow.size() != (size_t)p.kblocks * KB) return 2;
+    std::vector<int> seen(K, 0);
+    for (int k : p.krow) {
+        if (k < -1 || k >= K) return 2;
+        if (k >= 0 && seen[k]++) return 2;
+    }
+    for (int k = 0; k < K; ++k)
+        if (!seen[k]) return 2;
+    // 3-6: the segments, in the order the kernel walks them
+    if (p.seg.size() != ((size_t)p.kblocks * p.nchunks * p.WK + 1) * SW) return 3;
+    const bool banded = p.rows_mode == 2;
+    const long long lane_reach = banded ? p.span - 1 : (long long)p.Wp - 1 + p.span - 1;   // furthest position of a lane
+    size_t pos = 0, real = 0;
+    for (int kb = 0; kb < p.kblocks; ++kb)
+        for (int ch = 0; ch < p.nchunks; ++ch) {
+            const int c0 = ch * p.Cc, c1 = std::min(C, c0 + p.Cc);
+            for (int wk = 0; wk < p.WK; ++wk) {
+                const int* sg = &p.seg[(((size_t)kb * p.nchunks + ch) * p.WK + wk) * SW];
+                if ((size_t)sg[0] != pos) return 3;                       // segments are contiguous
+                for (int kk = 0; kk < p.KW; ++kk) {
+                    const int k = p.krow[(size_t)kb * KB + wk * p.KW + kk];
+                    const int nb = sg[1 + kk];
+                    if (k < 0) {
+                        if (nb != 0) return 4;
+                        continue;
+                    }
+                    const int* cb = csr.colidx.data() + csr.rowptr[k];
+                    const int* ce = csr.colidx.data() + csr.rowptr[k + 1];
+                    const int* lo = std::lower_bound(cb, ce, c0 * RS);
+                    const int* hi = std::lower_bound(cb, ce, c1 * RS);
+                    const int n = (int)(hi - lo);
+                    if (nb != cdiv(n, kBatch)) return 4;                  // batches of the row in this chunk
+                    if (pos + (size_t)nb * kBatch + kBatch > p.entries.size()) return 4;
+                    int last_off = 0;
+                    for (int t = 0; t < nb * kBatch; ++t) {
+                        const Entry& e = p.entries[pos + t];
+                        if (t < n) {
+                            const int col = lo[t];
+                            const int c = col / RS, r = (col / S) % R, sx = col % S;
+                            const float wv = csr.val32[(size_t)(lo + t - csr.colidx.data())];
+                            uint32_t wb;
+                            __builtin_memcpy(&wb, &wv, 4);
+                            const long long elem = (long long)(c - c0) * p.CS + (long long)r * p.pitch + sx;
+                            if (e.wbits != wb || (long long)e.off != elem * ub) return 5;   // weight and tap
+                            if (elem + lane_reach >= (long long)(c1 - c0) * p.CS) return 6;  // inside the chunk's tile
+                            last_off = e.off;
+                        } else if (e.wbits != 0u || e.off != last_off) {
+                            return 5;                                     // padding: weight zero, a tap already read
+                        }
+                    }
+                    pos += (size_t)nb * kBatch;
+                    real += (size_t)n;
+                }
+            }
+        }
+    if ((size_t)p.seg[(size_t)p.kblocks * p.nchunks * p.WK * SW] != pos) return 3;
+    if (real != csr.colidx.size()) return 7;                              // 7: every stored weight exactly once
+    return 0;
+}
+
 }  // namespace sc
