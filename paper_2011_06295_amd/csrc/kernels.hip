@@ -27,6 +27,8 @@
 // one and written to the other buffer after it (one barrier per chunk).
 #include <hip/hip_runtime.h>
 
+#include <atomic>
+
 #include "internal.h"
 
 namespace sc {
@@ -547,9 +549,18 @@ int launch_one(const KernelArgs& a, int grid, int threads, int lds_bytes, hipStr
     } else {
     auto fn = tile_kernel<T, V, KW, LP>;
     if (lds_bytes > 64 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(fn),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+        // more than 64 KB of dynamic LDS has to be allowed per kernel and device: once, for the whole 160 KB
+        static std::atomic<unsigned long long> allowed{0};   // one bit per device ordinal
+        int dev = 0;
+        hipError_t e = hipGetDevice(&dev);
         if (e != hipSuccess) return (int)e;
+        const unsigned long long bit = dev < 64 ? 1ull << dev : 0ull;
+        if (!(allowed.load(std::memory_order_relaxed) & bit)) {
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(fn),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+            if (e != hipSuccess) return (int)e;
+            allowed.fetch_or(bit, std::memory_order_relaxed);
+        }
     }
     hipLaunchKernelGGL(fn, dim3(grid), dim3(threads), lds_bytes, s, a);
     return (int)hipGetLastError();
