@@ -246,7 +246,8 @@ def test_random_shapes_with_random_launch_overrides(seed):
         w, m, x = rand_layer(rng, N, C, K, R, S, H, W, density=float(rng.choice([0.02, 0.1, 0.3, 0.7])))
         vmax = 8 if dtype == "f16" else 4
         launch = [int(rng.choice([0, 1, 2, 4, vmax])), int(rng.choice([0, 1, 2, 3, 4])), int(rng.choice([0, 1, 2, 3, 5, 8])),
-                  int(rng.choice([0, 1, 2, 4, 8, 16])), int(rng.choice([0, 0, 1, 2, 3, 7, 16])), 0, int(rng.choice([0, 1, 2]))]
+                  int(rng.choice([0, 1, 2, 4, 8, 16])), int(rng.choice([0, 0, 1, 2, 3, 7, 16])), 0, int(rng.choice([0, 1, 2])),
+                  0, int(rng.choice([0, 1, 2]))]
         if rng.integers(0, 3) == 0:
             launch = [0]
         layer = B.SparseConv(w, m, dtype=dtype, unify=unify)
