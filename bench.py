@@ -113,6 +113,9 @@ def main():
     ap.add_argument("--buffer-mib", type=int, default=512,
                     help="the timed steps go round copies of the resident activations that together hold at least "
                          "this much (at most 16 copies), so that the last-level cache cannot serve them; 0: one set")
+    ap.add_argument("--refine", type=int, default=1,
+                    help="1: after the measured launch choice, time each layer's choice, the cost estimate's first choice "
+                         "and both kinds of output store inside a pass and keep the fastest (0: skip)")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="after the timed steps, copy a device buffer of this size once (a kernel of known "
                          "traffic that calibrates rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
@@ -143,6 +146,8 @@ def main():
     # the last-level cache (256 MB), so that no step finds its operands left there by the one before;
     # the same loop on a single set is reported beside it as the cache-hot figure.
     nsets = net.make_buffer_sets(args.buffer_mib << 20) if args.buffer_mib > 0 else 1
+    if tune and args.refine:
+        net.refine_in_context()
 
     def timed(rotate):
         for i in range(args.warmup):
@@ -237,7 +242,7 @@ def main():
         "config": {"workload": f"{work.name}, batch {N}, {nl} sparse conv layer(s), conv only, inputs resident in HBM, {nsets} buffer set(s) in rotation",
                    "layers": nl, "batch": N, "total_macs": total_macs,
                    "launch": ((f"override {args.launch}; " if args.launch else "") +
-                              (f"measured best of {args.autotune} ranked candidates per layer" if tune
+                              (f"measured best of {args.autotune} ranked candidates per layer" + (", re-checked inside a pass" if args.refine else "") if tune
                                else "cost estimate"))},
         "roofline": roofline,
         "layers": layers,

@@ -220,6 +220,25 @@ def test_buffer_sets_in_rotation_give_the_same_outputs():
     net.close()
 
 
+def test_launch_choice_rechecked_inside_a_pass_keeps_the_results():
+    """harness.Network.refine_in_context pins, per layer, the fastest of the measured choice, the
+    estimate's first choice and both kinds of output store: whatever it pins, the outputs stay right."""
+    from paper_2011_06295_amd import workloads as wl
+    work = wl.vgg16(6, "f32")
+    net = _net(work)
+    net.run_chain(wl.make_input(work))
+    net.autotune(3)
+    net.make_buffer_sets(2 * sum(r.x.numel() * 4 + r.y.numel() * 4 for r in net.runs))
+    chosen = net.refine_in_context(steps=2)
+    assert len(chosen) == 13 and all(c["store"] in (1, 2) for c in chosen)
+    for r in net.runs:
+        r.y.fill_(float("nan"))
+    net.step(0)
+    for li in (0, 1, 6, 12):
+        check_layer_full(net.runs[li], net.host_weights[li], "f32", f"refined-{net.runs[li].spec.name}")
+    net.close()
+
+
 def test_config5_unify_flag_matches_plain_rows():
     """Ragged rows padded to a unified count with explicit zeros give the same numbers."""
     import torch
