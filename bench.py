@@ -113,6 +113,9 @@ def main():
     ap.add_argument("--buffer-mib", type=int, default=512,
                     help="the timed steps go round copies of the resident activations that together hold at least "
                          "this much (at most 16 copies), so that the last-level cache cannot serve them; 0: one set")
+    ap.add_argument("--unify", action="store_true",
+                    help="create the layers with the unify flag (rows padded with explicit zeros to the fullest row's "
+                         "count): `value` then counts the stored entries, `useful_value` the kept weights only")
     ap.add_argument("--refine", type=int, default=1,
                     help="1: after the measured launch choice, time each layer's choice, the cost estimate's first choice "
                          "and both kinds of output store inside a pass and keep the fastest (0: skip)")
@@ -130,7 +133,7 @@ def main():
     from paper_2011_06295_amd import harness, workloads as wl
 
     work, layer_ids = make_workload(args.workload)
-    net = harness.Network(work, layer_ids=layer_ids)
+    net = harness.Network(work, unify=args.unify, layer_ids=layer_ids)
     if args.launch:
         for r in net.runs:
             r.layer.set_launch([int(v) for v in args.launch.split(",")])
@@ -247,6 +250,11 @@ def main():
         "roofline": roofline,
         "layers": layers,
     }
+    if args.unify:
+        useful = sum(int(m.sum()) * r.spec.E * r.spec.F * N for (_, m), r in zip(net.host_weights, net.runs))
+        out["useful_value"] = 2.0 * useful / (ms_per_step * 1e-3) / 1e9
+        out["config"]["stored_entries"] = sum(r.nnz for r in net.runs)
+        out["config"]["kept_weights"] = sum(int(m.sum()) for _, m in net.host_weights)
     if args.compare_dense:
         rows = net.compare_with_dense()
         out["dense_comparison"] = {"layers": rows,
