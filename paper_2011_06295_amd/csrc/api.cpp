@@ -252,7 +252,17 @@ int sparse_conv_forward(sparse_conv_t h, const void* input, void* output,
             return SC_EUNSUPPORTED;
         if ((rc = sc::bind_device(h)) != SC_OK) return rc;
         if (!p->uploaded) {
-            if ((rc = sc::upload(h, p->entries, &p->d_entries)) != SC_OK) return rc;
+            {   // device image of the entry table: per batch the weights, then the offsets
+                std::vector<sc::Batch> image(p->entries.size() / sc::kBatch);
+                for (size_t b = 0; b < image.size(); ++b)
+                    for (int u = 0; u < sc::kBatch; ++u) {
+                        const sc::Entry& en = p->entries[b * sc::kBatch + u];
+                        image[b].w[u] = en.wbits;
+                        const unsigned long long o = (unsigned long long)(uint32_t)en.off << (32 * (u & 1));
+                        image[b].off2[u / 2] = (u & 1) ? (image[b].off2[u / 2] | o) : o;
+                    }
+                if ((rc = sc::upload(h, image, &p->d_entries)) != SC_OK) return rc;
+            }
             if ((rc = sc::upload(h, p->seg, &p->d_seg)) != SC_OK) return rc;
             if ((rc = sc::upload(h, p->krow, &p->d_krow)) != SC_OK) return rc;
             p->uploaded = true;
@@ -260,7 +270,7 @@ int sparse_conv_forward(sparse_conv_t h, const void* input, void* output,
         sc::KernelArgs a;
         a.x = input;
         a.y = output;
-        a.entries = static_cast<const sc::Entry*>(p->d_entries);
+        a.entries = static_cast<const uint32_t*>(p->d_entries);
         a.seg = static_cast<const int*>(p->d_seg);
         a.krow = static_cast<const int*>(p->d_krow);
         a.bias = h->d_bias;

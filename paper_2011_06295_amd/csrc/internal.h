@@ -73,6 +73,14 @@ struct Entry {
     int32_t off;
 };
 
+// A batch of kBatch entries as the kernel fetches it (the device image of the entry table):
+// the weights, then the offsets, two to a 64-bit word (the lower entry in the lower half).
+struct Batch {
+    uint32_t w[kBatch];
+    unsigned long long off2[kBatch / 2];
+};
+static_assert(sizeof(Batch) == kBatch * sizeof(Entry), "same bytes as the entries it holds");
+
 // Everything a forward call needs for one geometry.
 //
 // The batch is laid out (virtually) as one tall zero-padded image per channel:
@@ -143,7 +151,7 @@ FastDiv make_fastdiv(int d);
 struct KernelArgs {
     const void* x;
     void* y;
-    const Entry* entries;
+    const uint32_t* entries;   // device image: one Batch per kBatch entries
     const int* seg;
     const int* krow;
     const float* bias;   // [K] or null

@@ -46,6 +46,22 @@ __device__ __forceinline__ const SC_CONSTANT T* as_constant(const T* p)
 }
 #pragma clang diagnostic pop
 
+// LDS addressed by its 32-bit address: what a read takes is the sum the kernel formed, as it is
+// (a read through an ordinary pointer into the LDS array adds the array's address once more).
+#define SC_LDS __attribute__((address_space(3)))
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Wold-style-cast"
+__device__ __forceinline__ unsigned lds_address(const unsigned char* in_lds)
+{
+    return (unsigned)(unsigned long long)(const SC_LDS unsigned char*)(in_lds);
+}
+template <typename Vt>
+__device__ __forceinline__ Vt lds_read(unsigned address)
+{
+    return *(const SC_LDS Vt*)(address);
+}
+#pragma clang diagnostic pop
+
 // n / d for 0 <= n < 2^31 with the multiplier prepared on the host.
 __device__ __forceinline__ int fdiv(int n, const FastDiv& f)
 {
@@ -198,18 +214,21 @@ __global__ __launch_bounds__(1024) void tile_kernel(const KernelArgs a)
     int d_nb[KW];
 #pragma unroll
     for (int kk = 0; kk < KW; ++kk) d_nb[kk] = sg[1 + kk];
-    const SC_CONSTANT Entry* e = nullptr;
+    const SC_CONSTANT uint32_t* e = nullptr;   // 2 * kBatch dwords per batch
     int nb[KW];
-    Entry cur[kBatch];
+    Batch cur;
+    auto fetch_batch = [](Batch& b, const SC_CONSTANT uint32_t* p) __attribute__((always_inline)) {
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u) b.w[u] = p[u];
+        const SC_CONSTANT unsigned long long* q = reinterpret_cast<const SC_CONSTANT unsigned long long*>(p + kBatch);
+#pragma unroll
+        for (int u = 0; u < kBatch / 2; ++u) b.off2[u] = q[u];
+    };
     auto begin_chunk = [&](int ch) __attribute__((always_inline)) {
-        e = as_constant(a.entries) + d_start;
+        e = as_constant(a.entries) + 2 * (size_t)d_start;
 #pragma unroll
         for (int kk = 0; kk < KW; ++kk) nb[kk] = d_nb[kk];
-#pragma unroll
-        for (int u = 0; u < kBatch; ++u) {  // the table ends in kBatch slack entries
-            cur[u].wbits = e[u].wbits;
-            cur[u].off = e[u].off;
-        }
+        fetch_batch(cur, e);  // the table ends in kBatch slack entries
         if (ch + 1 < a.nchunks) {
             sg += sg_step;
             d_start = sg[0];
@@ -224,7 +243,7 @@ __global__ __launch_bounds__(1024) void tile_kernel(const KernelArgs a)
     // into L2 first.  The loaded value is only kept until the next wait for staged data.
     auto touch = [&]() __attribute__((always_inline)) -> unsigned {
         const int first = d_start + lane * 8;  // 8 entries = 64 bytes
-        return first < d_end ? reinterpret_cast<const unsigned*>(a.entries + first)[0] : 0u;
+        return first < d_end ? a.entries[2 * (size_t)first] : 0u;
     };
     auto retire = [](unsigned t) __attribute__((always_inline)) { asm volatile("" ::"v"(t)); };
 
@@ -367,7 +386,8 @@ __global__ __launch_bounds__(1024) void tile_kernel(const KernelArgs a)
     // half run, the LDS reads of the next half (and, in the first half, the
     // scalar fetch of B) are in flight; the wait at the end of a half therefore
     // finds them complete, and one wait serves LDS and scalar returns alike.
-    // Entry offsets are in bytes: one VOP2 add per read.
+    // Entry offsets are in bytes and come two to a 64-bit scalar: one 64-bit add of the lane's
+    // address (held twice, in both halves of a register pair) forms the addresses of two reads.
     constexpr int kGroup = 2;                          // entries whose reads are issued together
     constexpr int kGroups = kBatch / kGroup;           // even: the two read buffers alternate
     constexpr int kPosBytes = 64 * (int)sizeof(vec);   // LDS distance between a lane's successive positions
@@ -380,48 +400,49 @@ __global__ __launch_bounds__(1024) void tile_kernel(const KernelArgs a)
     };
     auto compute = [&](int base, bool prefetch) __attribute__((always_inline)) {
         vec xs[2][kGroup][LP];
-        auto gather = [&](vec(&x)[kGroup][LP], const Entry* E) __attribute__((always_inline)) {
+        static_assert(kGroup == 2, "a group is the two entries whose offsets share a 64-bit scalar");
+        // the lane's LDS address (of the tile element under its first position), in both halves
+        const unsigned lane_at = lds_address(smem) + (unsigned)base;
+        const unsigned long long base2 = ((unsigned long long)lane_at << 32) | lane_at;
+        auto gather = [&](vec(&x)[kGroup][LP], const Batch& E, int g) __attribute__((always_inline)) {
+            const unsigned long long at2 = base2 + E.off2[g];   // no carry between the halves: LDS addresses are small
 #pragma unroll
             for (int u = 0; u < kGroup; ++u) {
-                const unsigned char* at = smem + (base + E[u].off);
+                const unsigned at = (unsigned)(u ? at2 >> 32 : at2);
 #pragma unroll
-                for (int p = 0; p < LP; ++p) x[u][p] = *reinterpret_cast<const vec*>(at + p * kPosBytes);
+                for (int p = 0; p < LP; ++p) x[u][p] = lds_read<vec>(at + p * kPosBytes);
             }
         };
-        auto fma = [&](const vec(&x)[kGroup][LP], const Entry* E, float (&ac)[LP][V]) __attribute__((always_inline)) {
+        auto fma = [&](const vec(&x)[kGroup][LP], const Batch& E, int g, float (&ac)[LP][V]) __attribute__((always_inline)) {
 #pragma unroll
             for (int u = 0; u < kGroup; ++u) {
-                const float w = __uint_as_float(E[u].wbits);
+                const float w = __uint_as_float(E.w[g * kGroup + u]);
 #pragma unroll
                 for (int p = 0; p < LP; ++p)
 #pragma unroll
                     for (int v = 0; v < V; ++v) ac[p][v] = __builtin_fmaf(w, (float)VT::get(x[u][p], v), ac[p][v]);
             }
         };
-        gather(xs[0], cur);
+        gather(xs[0], cur, 0);
         arrived(xs[0]);
         // A step consumes batch A group by group: while the multiply-adds of group j run on one
         // read buffer, the reads of group j + 1 (after A's last group: B's first) fill the other,
         // and during the first group the scalar fetch of B is in flight as well.
-        auto step = [&](const Entry (&A)[kBatch], Entry (&B)[kBatch], float (&ac)[LP][V]) __attribute__((always_inline)) {
+        auto step = [&](const Batch& A, Batch& B, float (&ac)[LP][V]) __attribute__((always_inline)) {
 #pragma unroll
             for (int j = 0; j < kGroups; ++j) {
                 __builtin_amdgcn_sched_barrier(0);
                 if (j == 0) {
-                    gather(xs[1], A + kGroup);
-                    e += kBatch;
-#pragma unroll
-                    for (int u = 0; u < kBatch; ++u) {
-                        B[u].wbits = e[u].wbits;
-                        B[u].off = e[u].off;
-                    }
+                    gather(xs[1], A, 1);
+                    e += 2 * kBatch;
+                    fetch_batch(B, e);
                 } else if (j + 1 < kGroups) {
-                    gather(xs[(j + 1) & 1], A + (j + 1) * kGroup);
+                    gather(xs[(j + 1) & 1], A, j + 1);
                 } else {
-                    gather(xs[0], B);
+                    gather(xs[0], B, 0);
                 }
                 __builtin_amdgcn_sched_barrier(0);
-                fma(xs[j & 1], A + j * kGroup, ac);
+                fma(xs[j & 1], A, j, ac);
                 __builtin_amdgcn_sched_barrier(0);
                 arrived(xs[(j + 1) & 1]);
             }
@@ -432,7 +453,7 @@ __global__ __launch_bounds__(1024) void tile_kernel(const KernelArgs a)
 #pragma unroll
                 for (int t = kk * kStage / KW; t < (kk + 1) * kStage / KW; ++t) fetch_unit(t);
             }
-            Entry nxt[kBatch];
+            Batch nxt;
             int b = 0;
             for (; b + 2 <= nb[kk]; b += 2) {
                 step(cur, nxt, acc[kk]);
@@ -440,8 +461,7 @@ __global__ __launch_bounds__(1024) void tile_kernel(const KernelArgs a)
             }
             if (b < nb[kk]) {
                 step(cur, nxt, acc[kk]);
-#pragma unroll
-                for (int u = 0; u < kBatch; ++u) cur[u] = nxt[u];
+                cur = nxt;
             }
         }
     };
