@@ -85,7 +85,8 @@ void rows_per_wavefront(int nrows, int WP, int WK, int KW, std::vector<int>& roo
 //  * A step (kBatch stored weights of one output channel, for the 64 * LP positions
 //    of a wavefront) costs its SIMD kBatch * LP * V multiply-adds of ~4 clocks
 //    (fp16: the mixed-precision multiply-add takes ~4.4) plus ~4 clocks a weight
-//    for the address, and the CU's LDS kBatch * LP * 64 elements
+//    for the address (as fitted, before one 64-bit add came to serve two weights;
+//    the ranking holds with it), and the CU's LDS kBatch * LP * 64 elements
 //    at ~225 B/clk.  For 16-byte fp32 elements the two are about equal, and they
 //    overlap for the most part.
 //  * A SIMD's multiply-adds are those of the rows its wavefronts hold (see
