@@ -184,6 +184,17 @@ int sparse_conv_autotune(sparse_conv_t h, const void* input, void* output,
                          int max_candidates, float* best_us);
 
 /*
+ * sparse_conv_rank_launches - the candidates sparse_conv_autotune would time, for callers
+ * that measure in their own setting (inside a pass through a network, say): up to
+ * max_candidates launch configurations for the geometry, cheapest cost estimate first,
+ * within whatever sparse_conv_set_launch has pinned.  params receives 9 ints per
+ * candidate, in the order sparse_conv_set_launch takes them (each can be passed back to
+ * it as it is); *count the number written.  Needs no GPU.
+ */
+int sparse_conv_rank_launches(sparse_conv_t h, int N, int H, int W, int stride, int pad,
+                              int max_candidates, int* params, int* count);
+
+/*
  * sparse_conv_set_epilogue - what the store step does with a finished sum
  * (section 3: the sum over the filter is added to the bias of its output channel
  * and the activation function is applied).  Default: store the bare sum.

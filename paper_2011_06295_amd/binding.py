@@ -25,7 +25,7 @@ LIB_PATH = os.environ.get("SPARSECONV_LIBRARY") or os.path.join(
 EXPORTS = (
     "sparse_conv_create", "sparse_conv_output_shape", "sparse_conv_forward",
     "sparse_conv_get_csr", "sparse_conv_set_launch", "sparse_conv_get_launch", "sparse_conv_set_epilogue", "sparse_conv_autotune",
-    "sparse_conv_create_codebook", "sparse_conv_get_codebook", "sparse_conv_check_plan",
+    "sparse_conv_create_codebook", "sparse_conv_get_codebook", "sparse_conv_check_plan", "sparse_conv_rank_launches",
     "sparse_conv_last_hip_error", "sparse_conv_strerror", "sparse_conv_destroy",
 )
 
@@ -60,6 +60,7 @@ def _load():
     lib.sparse_conv_get_launch.argtypes = [vp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, ip]
     lib.sparse_conv_set_epilogue.argtypes = [vp, vp, C.c_uint]
     lib.sparse_conv_check_plan.argtypes = [vp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, ip]
+    lib.sparse_conv_rank_launches.argtypes = [vp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, ip, ip]
     lib.sparse_conv_autotune.argtypes = [vp, vp, vp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, vp, C.c_int,
                                          C.POINTER(C.c_float)]
     lib.sparse_conv_last_hip_error.argtypes = [vp]
@@ -187,6 +188,15 @@ def sparse_conv_get_launch(handle: int, N: int, H: int, W: int, stride: int, pad
     return dict(zip(names, list(arr)))
 
 
+def sparse_conv_rank_launches(handle: int, N: int, H: int, W: int, stride: int, pad: int, max_candidates: int = 8):
+    """The best-ranked launch configurations for a geometry, each a list of 9 ints that sparse_conv_set_launch takes."""
+    arr = (C.c_int * (9 * max_candidates))()
+    n = C.c_int(0)
+    _check(_lib.sparse_conv_rank_launches(handle, N, H, W, stride, pad, max_candidates, arr, C.byref(n)),
+           "sparse_conv_rank_launches", handle)
+    return [list(arr[9 * i:9 * i + 9]) for i in range(n.value)]
+
+
 def sparse_conv_check_plan(handle: int, N: int, H: int, W: int, stride: int, pad: int) -> int:
     """Host-side consistency check of the geometry's plan: 0, or the number of the first failed check."""
     bad = C.c_int(-1)
@@ -234,6 +244,9 @@ class SparseConv:
 
     def check_plan(self, N: int, H: int, W: int, stride: int = 1, pad: int = 0) -> int:
         return sparse_conv_check_plan(self.handle, N, H, W, stride, pad)
+
+    def rank_launches(self, N: int, H: int, W: int, stride: int = 1, pad: int = 0, max_candidates: int = 8):
+        return sparse_conv_rank_launches(self.handle, N, H, W, stride, pad, max_candidates)
 
     def set_launch(self, params: Sequence[int]):
         sparse_conv_set_launch(self.handle, params)

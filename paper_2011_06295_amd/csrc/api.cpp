@@ -409,6 +409,30 @@ int sparse_conv_autotune(sparse_conv_t h, const void* input, void* output,
     }
 }
 
+int sparse_conv_rank_launches(sparse_conv_t h, int N, int H, int W, int stride, int pad,
+                              int max_candidates, int* params, int* count)
+{
+    if (!h || N <= 0 || max_candidates <= 0 || !params || !count) return SC_EINVAL;
+    if (!sc::geometry_ok(h, H, W, stride, pad)) return SC_EINVAL;
+    try {
+        std::vector<std::pair<double, sc::Launch>> ranked;
+        sc::Plan scratch;
+        int rc = sc::build_plan(h->csr, h->C, h->R, h->S, h->dtype == SC_F16 ? 2 : 4, sc::Geometry{N, H, W, stride, pad},
+                                h->over, scratch, &ranked);
+        if (rc != SC_OK) return rc;
+        const int n = (int)std::min<size_t>(ranked.size(), (size_t)max_candidates);
+        for (int i = 0; i < n; ++i) {
+            const sc::Launch& l = ranked[i].second;
+            const int v[9] = {l.V, l.WP, l.WK, l.KW, l.Cc, 0, l.LP, l.kblocks, l.store ? l.store : 1};
+            std::memcpy(params + 9 * i, v, sizeof(v));
+        }
+        *count = n;
+        return SC_OK;
+    } catch (...) {
+        return SC_ENOMEM;
+    }
+}
+
 int sparse_conv_check_plan(sparse_conv_t h, int N, int H, int W, int stride, int pad, int* failed_check)
 {
     if (!h || N < 0) return SC_EINVAL;

@@ -77,51 +77,49 @@ class Network:
         return [run.layer.autotune(run.x, run.spec.stride, run.spec.pad, out=run.y, max_candidates=max_candidates)
                 for run in self.runs]
 
-    def refine_in_context(self, steps: int = 8):
-        """Second look at every layer's measured choice, inside a pass: sparse_conv_autotune times a
-        layer repeated on the same buffers, which flatters some configurations of the layers that are
-        bound by memory traffic.  Per layer the measured choice, the cost estimate's first choice and
-        both kinds of output store are run in pass order (going round the buffer sets if there are
-        any) with events around that layer only, and the fastest is pinned."""
+    def refine_in_context(self, steps: int = 8, top: int = 4):
+        """Second look at every layer's launch choice, inside a pass: sparse_conv_autotune times a
+        layer repeated on the same buffers (which stay in the last-level cache if they fit), and
+        that flatters some configurations.  Per layer the measured choice and the `top` candidates
+        the cost estimate ranks best are run in pass order (going round the buffer sets if there
+        are any) with events around that layer only; the two fastest are run once more with the
+        other kind of output store, and the fastest of all is pinned."""
         import torch
-        keys = ("V", "WP", "WK", "KW", "Cc", "LP", "kblocks", "store")
-
-        def pin(run, d):
-            run.layer.set_launch([d["V"], d["WP"], d["WK"], d["KW"], d["Cc"], 0, d["LP"], d["kblocks"], d["store"]])
 
         def geom(run):
             return (self.work.N, run.spec.H, run.spec.W, run.spec.stride, run.spec.pad)
 
+        def time_layer(li, launch):
+            self.runs[li].layer.set_launch(launch)
+            t = 0.0
+            for j in range(2 + steps):
+                sets = getattr(self, "sets", None)
+                bufs = sets[j % len(sets)] if sets else [(r.x, r.y) for r in self.runs]
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                for i, (r, (x, y)) in enumerate(zip(self.runs, bufs)):
+                    if i == li:
+                        e0.record()
+                    r.layer.forward(x, r.spec.stride, r.spec.pad, out=y)
+                    if i == li:
+                        e1.record()
+                torch.cuda.synchronize()
+                if j >= 2:
+                    t += e0.elapsed_time(e1)
+            return t
+
         for li, run in enumerate(self.runs):
-            tuned = {k: run.layer.get_launch(*geom(run))[k] for k in keys}
+            d = run.layer.get_launch(*geom(run))
+            tuned = [d["V"], d["WP"], d["WK"], d["KW"], d["Cc"], 0, d["LP"], d["kblocks"], d["store"]]
             run.layer.set_launch([])                 # back to the estimate (this discards the measured choice)
-            first = {k: run.layer.get_launch(*geom(run))[k] for k in keys}
-            cands = []
-            for base in (tuned, first):
-                for store in (1, 2):
-                    c = dict(base, store=store)
-                    if c not in cands:
-                        cands.append(c)
-            best = None
-            for c in cands:
-                pin(run, c)
-                t = 0.0
-                for j in range(2 + steps):
-                    sets = getattr(self, "sets", None)
-                    bufs = sets[j % len(sets)] if sets else [(r.x, r.y) for r in self.runs]
-                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                    for i, (r, (x, y)) in enumerate(zip(self.runs, bufs)):
-                        if i == li:
-                            e0.record()
-                        r.layer.forward(x, r.spec.stride, r.spec.pad, out=y)
-                        if i == li:
-                            e1.record()
-                    torch.cuda.synchronize()
-                    if j >= 2:
-                        t += e0.elapsed_time(e1)
-                if best is None or t < best[0]:
-                    best = (t, c)
-            pin(run, best[1])
+            cands = [tuned]
+            for c in run.layer.rank_launches(*geom(run), max_candidates=top):
+                if c[:8] not in [k[:8] for k in cands]:
+                    cands.append(c)
+            timed = sorted((time_layer(li, c), c) for c in cands)
+            for t, c in list(timed[:2]):
+                other = c[:8] + [3 - c[8]]
+                timed.append((time_layer(li, other), other))
+            run.layer.set_launch(min(timed)[1])
         return [run.layer.get_launch(*geom(run)) for run in self.runs]
 
     def make_buffer_sets(self, min_bytes: int = 512 << 20, max_sets: int = 16) -> int:

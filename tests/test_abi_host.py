@@ -253,3 +253,24 @@ def test_plans_of_the_benchmark_layers_are_consistent():
         layer = B.SparseConv(wl.make_weights(work.config, li, spec), wl.make_mask(work.config, li, spec), dtype="f32")
         _plan_ok(layer, work.N, spec.H, spec.W, spec.stride, spec.pad, f"{work.name} {spec.name}")
         layer.close()
+
+
+def test_ranked_launches_can_be_pinned_and_plan_consistently():
+    """sparse_conv_rank_launches lists what the measured choice would time: every candidate is accepted
+    by sparse_conv_set_launch as it is, yields the same configuration back, and its plan is consistent."""
+    from paper_2011_06295_amd import workloads as wl
+    work = wl.vgg16(128, "f32")
+    for li in (2, 6, 12):
+        spec = work.layers[li - 1]
+        layer = B.SparseConv(wl.make_weights(work.config, li, spec), wl.make_mask(work.config, li, spec), dtype="f32")
+        geom = (work.N, spec.H, spec.W, spec.stride, spec.pad)
+        first = layer.get_launch(*geom)
+        cands = layer.rank_launches(*geom, max_candidates=6)
+        assert 1 <= len(cands) <= 6 and len({tuple(c) for c in cands}) == len(cands)
+        assert [first[k] for k in ("V", "WP", "WK", "KW", "Cc", "LP", "kblocks")] == cands[0][:5] + cands[0][6:8]
+        for c in cands:
+            layer.set_launch(c)
+            got = layer.get_launch(*geom)
+            assert [got[k] for k in ("V", "WP", "WK", "KW", "Cc", "LP", "kblocks", "store")] == c[:5] + c[6:9]
+            _plan_ok(layer, *geom, f"{spec.name} {c}")
+        layer.close()
