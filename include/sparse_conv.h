@@ -167,11 +167,12 @@ int sparse_conv_set_launch(sparse_conv_t h, const int* params, int nparams);
 /*
  * sparse_conv_autotune - choose the launch configuration of one geometry by
  * measurement (section 8 sets the thread-block count of each layer by
- * experiment; section 9 reports what an untuned choice costs).  Runs the layer on the given buffers with the max_candidates
- * (<= 0: 8) configurations the cost estimate ranks best, within whatever
- * sparse_conv_set_launch has pinned, times each with events on `stream`, times
- * the three fastest once more with the other kind of output store, and keeps the
- * fastest for later forwards of this (N,H,W,stride,pad).
+ * experiment; section 9 reports what an untuned choice costs).  Runs the layer
+ * on the given buffers with the max_candidates (<= 0: 8) configurations the
+ * cost estimate ranks best, within whatever sparse_conv_set_launch has pinned,
+ * times each with events on `stream`, times the three fastest once more with
+ * non-temporal output stores (kept only where at least 2 % faster), and keeps
+ * the fastest for later forwards of this (N,H,W,stride,pad).
  *   input, output, N..pad, stream   as for sparse_conv_forward (N > 0); output is
  *            overwritten with the layer's result.
  *   best_us  if not NULL receives the kept configuration's time per launch, in us.
