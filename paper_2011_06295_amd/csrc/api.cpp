@@ -281,7 +281,7 @@ int sparse_conv_forward(sparse_conv_t h, const void* input, void* output,
         a.WP = p->WP; a.WK = p->WK; a.Cc = p->Cc;
         a.Wp = p->Wp; a.Hs = p->Hs; a.Hb = p->Hb; a.CS = p->CS; a.span = p->span;
         a.nchunks = p->nchunks; a.ngroups = p->ngroups; a.ntiles = p->ntiles; a.kblocks = p->kblocks;
-        a.tile_elems = p->Cc * p->CS;
+        a.tile_elems = p->Cc * p->CS + 1;
         a.SL = p->SL; a.rows_mode = p->rows_mode; a.tbl_off = p->tbl_off;
         a.SG = p->SG; a.SP = p->SP;
         a.nbuf = p->nbuf;

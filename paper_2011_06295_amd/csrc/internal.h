@@ -160,7 +160,7 @@ struct KernelArgs {
     int N, C, H, W, K, E, F, stride, pad;
     int WP, WK, Cc, Wp, Hs, Hb, CS, span;
     int nchunks, ngroups, ntiles, kblocks;
-    int tile_elems;  // Cc * CS
+    int tile_elems;  // elements from one tile buffer to the next: Cc * CS and a spare one
     // staging: a channel of the tile is SG groups of SP slots (SL = SG * SP); units are
     // ordered (group, channel, slot-in-group) and a thread's next unit is nthreads further on
     int SL;          // slots of one channel

@@ -60,6 +60,11 @@ __device__ __forceinline__ Vt lds_read(unsigned address)
 {
     return *(const SC_LDS Vt*)(address);
 }
+template <typename Vt>
+__device__ __forceinline__ void lds_write(unsigned address, const Vt& value)
+{
+    *(SC_LDS Vt*)(address) = value;
+}
 #pragma clang diagnostic pop
 
 // n / d for 0 <= n < 2^31 with the multiplier prepared on the host.
@@ -247,10 +252,11 @@ __global__ __launch_bounds__(1024) void tile_kernel(const KernelArgs a)
     };
     auto retire = [](unsigned t) __attribute__((always_inline)) { asm volatile("" ::"v"(t)); };
 
-    // ---- LDS: nbuf tile buffers (two when the channels come in several chunks), one
-    // reject element, the slot table
+    // ---- LDS: nbuf tile buffers (two when the channels come in several chunks), each followed by
+    // one spare element (where staging units without a real element are written), the slot table
     vec* tile = reinterpret_cast<vec*>(smem);
-    const int reject = a.nbuf * a.tile_elems;
+    const int reject = a.tile_elems - 1;   // the spare element, relative to a buffer
+    const unsigned tile_at = lds_address(smem);
 
     // Staging table.  What a tile holds of one channel is the same for every
     // channel: a set of SL slots, each one real (non-padding) element of the
@@ -309,9 +315,9 @@ __global__ __launch_bounds__(1024) void tile_kernel(const KernelArgs a)
     // channels load whatever follows in memory (or zero past the end) into tile channels
     // that no plan entry refers to.
     vec st_val[kStage];
-    int st_dst[kStage];            // tile element of the unit in flight
+    unsigned st_dst[kStage];       // where the unit in flight goes: LDS address in the first tile buffer
     unsigned u_off[kStage];        // first pass: source offset (0x80000000: none) ...
-    int u_dst[kStage];             // ... and tile element (the reject element if none)
+    unsigned u_dst[kStage];        // ... and LDS address in the first buffer (the spare element if none)
     int gi = 0, c = 0, sp = 0;     // later passes: the thread's next unit
     int f_cn = 0;                  // later passes: channels of the chunk being fetched
     __amdgpu_buffer_rsrc_t f_rs = chunk_rsrc(0);
@@ -335,7 +341,7 @@ __global__ __launch_bounds__(1024) void tile_kernel(const KernelArgs a)
             const int2 sd = tbl[in ? (int)__umul24(gi, a.SP) + sp : 0];
             const bool ok = in && sd.x >= 0;
             u_off[t] = ok ? (unsigned)sd.x + (unsigned)c * chan_bytes : 0x80000000u;
-            u_dst[t] = ok ? sd.y + (int)__umul24(c, a.CS) : reject;
+            u_dst[t] = tile_at + (unsigned)(ok ? sd.y + (int)__umul24(c, a.CS) : reject) * (unsigned)sizeof(vec);
             next_unit();
         }
     };
@@ -366,17 +372,17 @@ __global__ __launch_bounds__(1024) void tile_kernel(const KernelArgs a)
             const int2 sd = tbl[in ? (int)__umul24(gi, a.SP) + sp : 0];
             const bool ok = in && sd.x >= 0;
             const unsigned off = ok ? (unsigned)sd.x + (unsigned)c * chan_bytes : 0x80000000u;
-            st_dst[t] = ok ? sd.y + (int)__umul24(c, a.CS) : reject;
+            st_dst[t] = tile_at + (unsigned)(ok ? sd.y + (int)__umul24(c, a.CS) : reject) * (unsigned)sizeof(vec);
 #pragma unroll
             for (int v = 0; v < V; ++v) VT::set(st_val[t], v, load_elem<T>(f_rs, off + (unsigned)v * img_bytes));
             next_unit();
         }
     };
     auto deposit = [&](int buf) __attribute__((always_inline)) {
-        const int base = buf * a.tile_elems;
+        const unsigned base = (unsigned)(buf * a.tile_elems) * (unsigned)sizeof(vec);
 #pragma unroll
-        for (int t = 0; t < kStage; ++t)  // unconditional (rejects go to a spare element): no branches between the writes
-            tile[st_dst[t] == reject ? reject : base + st_dst[t]] = st_val[t];
+        for (int t = 0; t < kStage; ++t)  // unconditional (units without an element go to the buffer's spare one): one add a write
+            lds_write<vec>(st_dst[t] + base, st_val[t]);
     };
 
     // Gather-FMA over this wavefront's KW rows of one chunk whose tile starts at
@@ -477,7 +483,7 @@ __global__ __launch_bounds__(1024) void tile_kernel(const KernelArgs a)
     begin_chunk(0);
     // while the first loads are in flight: padding rows/columns and absent images are zeroed
     // once and stay zero for the whole kernel (staging writes real elements only)
-    for (int u = tid; u < reject; u += nthreads) tile[u] = VT::zero();
+    for (int u = tid; u < a.nbuf * a.tile_elems; u += nthreads) tile[u] = VT::zero();
     __syncthreads();  // zero fill complete
     deposit(0);
     for (int p = 1; p < a.npass; ++p) {

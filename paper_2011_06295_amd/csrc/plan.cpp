@@ -259,8 +259,8 @@ int build_plan(const Csr& csr, int C, int R, int S, int elem_bytes, const Geomet
                         if (Cc < 1) continue;
                         if (!over.Cc) Cc = cdiv(C, cdiv(C, Cc));     // even chunks
                         if (Cc < C) nbuf = 2;                        // the next chunk lands while this one is consumed
-                        // tile buffer(s), one reject element, table
-                        const long long lds = (((long long)nbuf * Cc * CS + 1) * s.ub + 15) / 16 * 16 + tbl;
+                        // tile buffer(s), each with one spare element, table
+                        const long long lds = ((long long)nbuf * ((long long)Cc * CS + 1) * s.ub + 15) / 16 * 16 + tbl;
                         if (lds > kMaxLds) continue;
                         // More channel blocks than the rows need leave slots empty, which relieves the
                         // last wavefronts of the fullest SIMDs (rows_per_wavefront): up to two extra.
@@ -332,7 +332,7 @@ int build_plan(const Csr& csr, int C, int R, int S, int elem_bytes, const Geomet
     p.rows_mode = best.rows_mode;
     p.pitch = best.pitch;
     p.nbuf = best.nbuf;
-    p.tbl_off = ((p.nbuf * p.Cc * p.CS + 1) * s.ub + 15) / 16 * 16;
+    p.tbl_off = (p.nbuf * (p.Cc * p.CS + 1) * s.ub + 15) / 16 * 16;
     const long long grid = (ntiles * p.kblocks + 7) / 8 * 8;   // a multiple of the XCD count
     if (ntiles > INT_MAX / 2 || grid > INT_MAX - 8) return SC_EUNSUPPORTED;
     p.ntiles = (int)ntiles;
@@ -451,7 +451,7 @@ int check_plan(const Csr& csr, int C, int R, int S, int elem_bytes, const Plan& 
     if (p.threads != kWave * p.WP * p.WK || p.threads > kWave * kMaxWaves || p.lds_bytes > kMaxLds) return 1;
     if (p.nchunks != cdiv(C, p.Cc) || (p.nbuf != 1 && p.nbuf != 2) || (p.nchunks > 1 && p.nbuf != 2)) return 1;
     if ((long long)p.tbl_off + (long long)p.SL * 8 > p.lds_bytes) return 1;
-    if (((long long)p.nbuf * p.Cc * p.CS + 1) * ub > p.tbl_off) return 1;
+    if ((long long)p.nbuf * ((long long)p.Cc * p.CS + 1) * ub > p.tbl_off) return 1;
     if ((long long)p.grid < (long long)p.ntiles * p.kblocks || p.grid % 8 != 0) return 1;
     if ((long long)p.ntiles * p.span < p.npos || (long long)(p.ntiles - 1) * p.span >= p.npos) return 1;
     // 2: every output channel owns exactly one accumulator slot
