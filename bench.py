@@ -62,7 +62,7 @@ def layer_roofs(run, N, b):
 
 
 # mean HBM-side bytes per launch of sc::tile_kernel (see profiles/)
-MEASURED_TRAFFIC = {"vgg16_f32": 28.6e6, "vgg16_f16": 30.2e6}
+MEASURED_TRAFFIC = {"vgg16_f32": 27.7e6, "vgg16_f16": 31.1e6}
 
 
 def cpu_baseline(net, work, budget_s=12.0):
