@@ -354,7 +354,7 @@ __global__ __launch_bounds__(1024) void tile_kernel(const KernelArgs a)
         st_dst[t] = u_dst[t];
         unsigned ib = img_bytes;
         // with many accumulators, keep the V offsets of all units from being worked out once and held in registers
-        if constexpr (KW * LP * V > 16) asm volatile("" : "+s"(ib));
+        if constexpr (KW * LP * V > 16 || LP * V > 8) asm volatile("" : "+s"(ib));
 #pragma unroll
         for (int v = 0; v < V; ++v) VT::set(st_val[t], v, load_elem<T>(f_rs, u_off[t] + (unsigned)v * ib));
     };
