@@ -571,7 +571,7 @@ template <typename T, int V, int KW, int LP>
 int launch_one(const KernelArgs& a, int grid, int threads, int lds_bytes, hipStream_t s)
 {
     // accumulators (KW * LP * V floats) plus the reads in flight have to fit a 128-register wavefront
-    if constexpr (LP > 1 && KW * LP * V > 32) {
+    if constexpr ((LP > 1 && KW * LP * V > 32) || KW * V > 64) {
         return (int)hipErrorInvalidValue;
     } else {
     auto fn = tile_kernel<T, V, KW, LP>;
