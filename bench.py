@@ -113,6 +113,8 @@ def main():
     ap.add_argument("--buffer-mib", type=int, default=512,
                     help="the timed steps go round copies of the resident activations that together hold at least "
                          "this much (at most 16 copies), so that the last-level cache cannot serve them; 0: one set")
+    ap.add_argument("--refine-top", type=int, default=4,
+                    help="best-ranked candidates the second look times beside the measured choice")
     ap.add_argument("--unify", action="store_true",
                     help="create the layers with the unify flag (rows padded with explicit zeros to the fullest row's "
                          "count): `value` then counts the stored entries, `useful_value` the kept weights only")
@@ -150,7 +152,7 @@ def main():
     # the same loop on a single set is reported beside it as the cache-hot figure.
     nsets = net.make_buffer_sets(args.buffer_mib << 20) if args.buffer_mib > 0 else 1
     if tune and args.refine:
-        net.refine_in_context()
+        net.refine_in_context(top=args.refine_top)
 
     def timed(rotate):
         for i in range(args.warmup):
