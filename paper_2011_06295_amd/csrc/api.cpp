@@ -2,6 +2,7 @@
 #include <hip/hip_runtime_api.h>
 
 #include <algorithm>
+#include <cstdint>
 #include <cstring>
 #include <new>
 #include <utility>
@@ -52,6 +53,16 @@ int get_plan(sparse_conv_s* h, const Geometry& g, Plan** out)
     }
     *out = it->second.get();
     return SC_OK;
+}
+
+// True if the input [N][C][H][W] and the output [N][K][E][F] of a call share any byte.
+bool buffers_overlap(const sparse_conv_s* h, const void* input, const void* output, int N, int H, int W, int stride, int pad)
+{
+    const size_t b = h->dtype == SC_F16 ? 2 : 4;
+    const size_t E = (size_t)((H + 2 * pad - h->R) / stride + 1), F = (size_t)((W + 2 * pad - h->S) / stride + 1);
+    const uintptr_t i0 = reinterpret_cast<uintptr_t>(input), o0 = reinterpret_cast<uintptr_t>(output);
+    const uintptr_t i1 = i0 + (size_t)N * h->C * H * W * b, o1 = o0 + (size_t)N * h->K * E * F * b;
+    return i0 < o1 && o0 < i1;
 }
 
 // A handle's device buffers (plan tables, bias) live on the device that was current when the
@@ -250,6 +261,7 @@ int sparse_conv_forward(sparse_conv_t h, const void* input, void* output,
         // the kernels index both tensors with 32-bit element offsets
         if ((long long)N * h->C * H * W >= (1ll << 31) || (long long)N * h->K * p->E * p->F >= (1ll << 31))
             return SC_EUNSUPPORTED;
+        if (sc::buffers_overlap(h, input, output, N, H, W, stride, pad)) return SC_EINVAL;
         if ((rc = sc::bind_device(h)) != SC_OK) return rc;
         if (!p->uploaded) {
             {   // device image of the entry table: per batch the weights, then the offsets
@@ -322,10 +334,33 @@ int sparse_conv_autotune(sparse_conv_t h, const void* input, void* output,
                          int N, int H, int W, int stride, int pad, void* stream,
                          int max_candidates, float* best_us)
 {
-    if (!h || N <= 0 || !input || !output || input == output) return SC_EINVAL;
+    if (!h || N <= 0 || !input || !output) return SC_EINVAL;
     if (!sc::geometry_ok(h, H, W, stride, pad)) return SC_EINVAL;
+    if (sc::buffers_overlap(h, input, output, N, H, W, stride, pad)) return SC_EINVAL;
+    const sc::Geometry g{N, H, W, stride, pad};
+    // Whatever happens below (an exception included), the handle gets its override back, the
+    // candidate's plan is dropped and the events are released; an earlier measured choice for the
+    // geometry is set aside while the candidates run and comes back unless a new one replaces it.
+    struct Restore {
+        sparse_conv_s* h;
+        sc::Geometry g;
+        sc::Launch saved;
+        bool had_tuned = false;
+        sc::Launch old_tuned;
+        hipEvent_t e0 = nullptr, e1 = nullptr;
+        bool replaced = false;
+        ~Restore()
+        {
+            if (e0) (void)hipEventDestroy(e0);
+            if (e1) (void)hipEventDestroy(e1);
+            h->over = saved;
+            h->plans.erase(g);
+            if (had_tuned && !replaced) {
+                try { h->tuned[g] = old_tuned; } catch (...) {}
+            }
+        }
+    } restore{h, g, h->over};
     try {
-        const sc::Geometry g{N, H, W, stride, pad};
         std::vector<std::pair<double, sc::Launch>> ranked;
         sc::Plan scratch;
         int rc = sc::build_plan(h->csr, h->C, h->R, h->S, h->dtype == SC_F16 ? 2 : 4, g, h->over, scratch, &ranked);
@@ -333,16 +368,22 @@ int sparse_conv_autotune(sparse_conv_t h, const void* input, void* output,
         const size_t want = max_candidates > 0 ? (size_t)max_candidates : 8;
         if (ranked.size() > want) ranked.resize(want);
         hipStream_t s = static_cast<hipStream_t>(stream);
-        hipEvent_t e0 = nullptr, e1 = nullptr;
-        hipError_t he = hipEventCreate(&e0);
-        if (he == hipSuccess) he = hipEventCreate(&e1);
+        hipError_t he = hipEventCreate(&restore.e0);
+        if (he == hipSuccess) he = hipEventCreate(&restore.e1);
         if (he != hipSuccess) {
-            if (e0) (void)hipEventDestroy(e0);
             h->last_hip = (int)he;
             return SC_EHIP;
         }
-        const sc::Launch saved = h->over;
-        h->tuned.erase(g);   // an earlier choice for this geometry must not stand in for the candidates
+        hipEvent_t e0 = restore.e0, e1 = restore.e1;
+        const sc::Launch saved = restore.saved;
+        {   // an earlier choice for this geometry must not stand in for the candidates
+            auto old = h->tuned.find(g);
+            if (old != h->tuned.end()) {
+                restore.had_tuned = true;
+                restore.old_tuned = old->second;
+                h->tuned.erase(old);
+            }
+        }
         sc::Launch best_launch;
         float best = -1.f;
         rc = SC_OK;
@@ -393,13 +434,10 @@ int sparse_conv_autotune(sparse_conv_t h, const void* input, void* output,
                 if (rc == SC_OK && ms >= 0.f && ms < 0.98f * ordinary && ms < best) { best = ms; best_launch = l; }
             }
         }
-        (void)hipEventDestroy(e0);
-        (void)hipEventDestroy(e1);
-        h->over = saved;
-        h->plans.erase(g);
         if (rc != SC_OK) return rc;
         if (best < 0.f) return SC_EUNSUPPORTED;
         h->tuned[g] = best_launch;
+        restore.replaced = true;
         if (best_us) *best_us = best * 1000.f / 5.f;
         return SC_OK;
     } catch (const std::bad_alloc&) {

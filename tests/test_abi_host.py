@@ -109,6 +109,11 @@ def test_argument_validation_returns_status_codes():
     assert lib.sparse_conv_autotune(None, 8, 16, 1, 4, 4, 1, 0, None, 0, None) == B.SC_EINVAL    # arguments are checked before any GPU call
     assert lib.sparse_conv_autotune(h, None, 16, 1, 4, 4, 1, 0, None, 0, None) == B.SC_EINVAL
     assert lib.sparse_conv_autotune(h, 8, 8, 1, 4, 4, 1, 0, None, 0, None) == B.SC_EINVAL         # in place
+    # partial overlap of input [1][3][4][4] (192 bytes from 4096) and output [1][2][2][2] (32 bytes)
+    assert lib.sparse_conv_autotune(h, 4096, 4096 + 188, 1, 4, 4, 1, 0, None, 0, None) == B.SC_EINVAL
+    assert lib.sparse_conv_autotune(h, 4096, 4096 - 28, 1, 4, 4, 1, 0, None, 0, None) == B.SC_EINVAL
+    assert lib.sparse_conv_forward(h, 4096, 4096 + 188, 1, 4, 4, 1, 0, None) == B.SC_EINVAL
+    assert lib.sparse_conv_forward(h, 4096, 4096 - 28, 1, 4, 4, 1, 0, None) == B.SC_EINVAL
     assert lib.sparse_conv_autotune(h, 8, 16, 0, 4, 4, 1, 0, None, 0, None) == B.SC_EINVAL        # needs a batch to time
     assert lib.sparse_conv_autotune(h, 8, 16, 1, 4, 4, 0, 0, None, 0, None) == B.SC_EINVAL        # stride 0
     assert lib.sparse_conv_strerror(B.SC_EINVAL) == b"invalid argument"

@@ -332,6 +332,39 @@ def test_ones_everywhere_counts_taps():
     assert (out[0, 0] == want).all() and (out[0, 1] == want).all()
 
 
+def test_sum_of_magnitudes_output():
+    # The optional second output is sum |w * x| over the stored taps of each output element (the
+    # scale a rounding-error bound for eq. 1 is relative to).  Pinned three ways: an independent numpy
+    # statement of eq. 1 on the magnitudes (dense einsum over the padded input), the closed form for
+    # a constant input without padding (sum of |w| over the row), and |out| <= abs_out with equality
+    # where all products have one sign.
+    rng = np.random.default_rng(77)
+    N, C, K, R, S, H, W, st, p = 2, 3, 4, 3, 2, 6, 5, 2, 1
+    w, m, x = rand_layer(rng, N, C, K, R, S, H, W)
+    csr = oracle.csr_encode(w, m)
+    out, aout = oracle.sparse_conv(csr, x, K, R, S, st, p, want_abs=True)
+    E, F = out.shape[2:]
+    xp = np.zeros((N, C, H + 2 * p, W + 2 * p))
+    xp[:, :, p:p + H, p:p + W] = np.abs(x.astype(np.float64))
+    wa = np.abs((w * m).astype(np.float64))
+    ref = np.zeros((N, K, E, F))
+    for r in range(R):
+        for s_ in range(S):
+            patch = xp[:, :, r:r + (E - 1) * st + 1:st, s_:s_ + (F - 1) * st + 1:st]
+            ref += np.einsum("kc,ncij->nkij", wa[:, :, r, s_], patch)
+    np.testing.assert_allclose(aout, ref, rtol=2e-7, atol=0)
+    assert (np.abs(out) <= aout * (1 + 1e-6)).all()
+    # one sign everywhere: the two outputs coincide
+    out2, aout2 = oracle.sparse_conv(oracle.csr_encode(np.abs(w), m), np.abs(x), K, R, S, st, p, want_abs=True)
+    assert (out2 == aout2).all() and (aout2 == aout).all()
+    # constant input, no padding: sum of |w| over the row
+    ones = np.ones((1, C, H, W), dtype=np.float32)
+    _, a3 = oracle.sparse_conv(csr, ones, K, R, S, 1, 0, want_abs=True)
+    rowptr, _, values = csr
+    for k in range(K):
+        assert (a3[0, k] == np.float32(np.abs(values[rowptr[k]:rowptr[k + 1]].astype(np.float64)).sum())).all()
+
+
 @pytest.mark.parametrize("st,p", [(1, 0), (1, 1), (2, 1), (3, 2), (2, 0)])
 def test_delta_input_reads_back_the_filter(st, p):
     # x = delta at (c0,y0,x0): Out[k][i][j] = (w*mask)[k][c0][y0 - i*st + p][x0 - j*st + p] where that index exists
