@@ -32,6 +32,7 @@ class Network:
     def __init__(self, work: wl.Workload, unify: bool = False, layer_ids: Optional[List[int]] = None):
         self.work = work
         self.layer_ids = layer_ids
+        self.unified = unify
         self.runs: List[LayerRun] = []
         self.host_weights = []
         for li, spec in enumerate(work.layers, 1):

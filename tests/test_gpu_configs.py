@@ -1,7 +1,8 @@
-"""GPU parity on the five benchmark configurations, in the launch configuration
-bench.py times.  Small cases are compared element by element; at full batch
-size the oracle evaluates sampled output coordinates one by one (exact-order
-double sums of the same operands the GPU layer received)."""
+"""GPU parity on the five benchmark configurations.  Small cases are compared element by
+element; at full batch size the oracle evaluates sampled output coordinates one by one
+(exact-order double sums of the same operands the GPU layer received), once with the launch
+the cost estimate picks and once with the launches bench.py times (measured choice of 8
+candidates per layer, re-checked inside a pass over rotating buffer sets)."""
 import numpy as np
 import pytest
 
@@ -236,6 +237,56 @@ def test_launch_choice_rechecked_inside_a_pass_keeps_the_results():
     net.step(0)
     for li in (0, 1, 6, 12):
         check_layer_full(net.runs[li], net.host_weights[li], "f32", f"refined-{net.runs[li].spec.name}")
+    net.close()
+
+
+def _tune_as_bench_does(net):
+    """The launch selection of bench.py's default run, step by step."""
+    net.autotune(8)
+    net.make_buffer_sets(512 << 20)
+    return net.refine_in_context(top=4)
+
+
+@pytest.mark.parametrize("dtype,N", [("f32", 128), ("f16", 256)])
+def test_vgg_full_batch_in_the_launches_the_bench_times(dtype, N):
+    """Configs 3 and 4 at full batch with the measured, re-checked launch of every layer (what
+    bench.py times): all 13 layers against the oracle on sampled outputs, after a pass over
+    the second buffer set as well as the first."""
+    import torch
+    from paper_2011_06295_amd import workloads as wl
+    work = wl.vgg16(N, dtype)
+    net = _net(work)
+    net.run_chain(wl.make_input(work))
+    chosen = _tune_as_bench_does(net)
+    for which in (0, 1):
+        for _, y in net.sets[which % len(net.sets)]:
+            y.fill_(float("nan"))
+        net.step(which)
+        torch.cuda.synchronize()
+        for li, run in enumerate(net.runs):
+            x, y = net.sets[which % len(net.sets)][li]
+            run_view = type("View", (), {"spec": run.spec, "x": x, "y": y})
+            err = check_layer_sampled(run_view, net.host_weights[li], dtype, f"timed-vgg{N}-{dtype}-{run.spec.name}",
+                                      npts=2000, seed=100 + li)
+            if which == 0:
+                print(f"timed launch vgg batch {N} {dtype} {run.spec.name}: {chosen[li]} max err / max|ref| = {err:.3g}",
+                      flush=True)
+    net.close()
+
+
+@pytest.mark.parametrize("sparsity_bp", [9000, 9500, 9900])
+def test_sweep_layer_in_the_launch_the_bench_times(sparsity_bp):
+    import torch
+    from paper_2011_06295_amd import workloads as wl
+    work = wl.sweep_layer(sparsity_bp, False, 256)
+    net = _net(work, layer_ids=[wl.sweep_layer_index(sparsity_bp, False)])
+    net.run_chain(wl.make_input(work))
+    chosen = _tune_as_bench_does(net)
+    net.runs[0].y.fill_(float("nan"))
+    net.step(0)
+    torch.cuda.synchronize()
+    err = check_layer_sampled(net.runs[0], net.host_weights[0], "f32", f"timed-sweep-{sparsity_bp}", npts=2000, seed=sparsity_bp)
+    print(f"timed launch sweep {sparsity_bp}: {chosen[0]} max err / max|ref| = {err:.3g}", flush=True)
     net.close()
 
 
