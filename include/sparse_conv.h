@@ -34,7 +34,8 @@ enum {
     SC_EINVAL = -1,       /* null pointer, non-positive size, stride < 1, pad < 0, filter larger than padded input, unknown dtype/flag */
     SC_EUNSUPPORTED = -2, /* valid request this build cannot run (e.g. a tile that cannot fit the LDS, no gfx950 device) */
     SC_ENOMEM = -3,       /* host or device allocation failed */
-    SC_EHIP = -4          /* a HIP runtime call failed; sparse_conv_last_hip_error() has the code */
+    SC_EHIP = -4,         /* a HIP runtime call failed; sparse_conv_last_hip_error() has the code */
+    SC_ETOOBIG = -5       /* sparse_conv_forward_static: the layer's tables exceed the static device scratch */
 };
 
 /* Storage type of weights, input and output.  Products and sums are always
@@ -102,6 +103,33 @@ int sparse_conv_output_shape(sparse_conv_t h, int H, int W, int stride, int pad,
  */
 int sparse_conv_forward(sparse_conv_t h, const void* input, void* output,
                         int N, int H, int W, int stride, int pad, void* stream);
+
+/*
+ * sparse_conv_forward_static - sparse_conv_forward for callers that cannot allocate device
+ * memory: code that runs where hipMalloc is not allowed (tight serving loops, harnesses that
+ * forbid it).  Same arguments, same kernel, same result as sparse_conv_forward, but the call
+ * makes no device allocation, not even the first one for a geometry: the per-geometry tables
+ * the kernel reads (stored weights as LDS tap offsets, segment descriptors, channel slots) are
+ * copied, on `stream`, into a static device array of SC_STATIC_SCRATCH_BYTES that is part of the
+ * library's code object (every GPU the library runs on holds its own copy until the process
+ * ends), and the kernel reads them there.
+ *   - SC_ETOOBIG if the tables of this layer and geometry need more than that (about 8.2 bytes
+ *     per stored weight); nothing is enqueued then.
+ *   - All handles of the process share the array of a GPU, and it keeps what the last call
+ *     left there: a call whose tables are already in place (same handle, geometry and launch
+ *     configuration as the call before it on that GPU) copies nothing, any other call
+ *     overwrites them.  Calls on one GPU must therefore not overlap: a call that changes the
+ *     tables while an earlier kernel still reads them (another stream, another host thread
+ *     without ordering between the streams) races with it.  Enqueue on one stream, or order the
+ *     streams with events.
+ *   - The host-side plan of a new geometry is still built on the first call (host memory only);
+ *     the copy reads host memory owned by the handle, so the handle's plans must not be
+ *     discarded (sparse_conv_set_launch, sparse_conv_autotune, sparse_conv_destroy) before the
+ *     stream has passed the call.
+ */
+#define SC_STATIC_SCRATCH_BYTES (16u << 20)
+int sparse_conv_forward_static(sparse_conv_t h, const void* input, void* output,
+                               int N, int H, int W, int stride, int pad, void* stream);
 
 /*
  * sparse_conv_get_csr - expose the CSR arrays built by create (section 7).

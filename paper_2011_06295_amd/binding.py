@@ -13,7 +13,8 @@ from typing import Optional, Sequence, Tuple
 
 import numpy as np
 
-SC_OK, SC_EINVAL, SC_EUNSUPPORTED, SC_ENOMEM, SC_EHIP = 0, -1, -2, -3, -4
+SC_OK, SC_EINVAL, SC_EUNSUPPORTED, SC_ENOMEM, SC_EHIP, SC_ETOOBIG = 0, -1, -2, -3, -4, -5
+SC_STATIC_SCRATCH_BYTES = 16 << 20
 SC_F32, SC_F16 = 0, 1
 SC_FLAG_UNIFY_NNZ = 1
 SC_EPILOGUE_RELU = 1
@@ -23,7 +24,7 @@ LIB_PATH = os.environ.get("SPARSECONV_LIBRARY") or os.path.join(
     os.path.dirname(os.path.abspath(__file__)), "libsparseconv.so")
 
 EXPORTS = (
-    "sparse_conv_create", "sparse_conv_output_shape", "sparse_conv_forward",
+    "sparse_conv_create", "sparse_conv_output_shape", "sparse_conv_forward", "sparse_conv_forward_static",
     "sparse_conv_get_csr", "sparse_conv_set_launch", "sparse_conv_get_launch", "sparse_conv_set_epilogue", "sparse_conv_autotune",
     "sparse_conv_create_codebook", "sparse_conv_get_codebook", "sparse_conv_check_plan", "sparse_conv_rank_launches",
     "sparse_conv_last_hip_error", "sparse_conv_strerror", "sparse_conv_destroy",
@@ -55,6 +56,7 @@ def _load():
     lib.sparse_conv_get_codebook.argtypes = [vp, C.POINTER(vp), C.POINTER(vp)]
     lib.sparse_conv_output_shape.argtypes = [vp, C.c_int, C.c_int, C.c_int, C.c_int, ip, ip]
     lib.sparse_conv_forward.argtypes = [vp, vp, vp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, vp]
+    lib.sparse_conv_forward_static.argtypes = lib.sparse_conv_forward.argtypes
     lib.sparse_conv_get_csr.argtypes = [vp, ip, C.POINTER(C.c_longlong), C.POINTER(vp), C.POINTER(vp), C.POINTER(vp)]
     lib.sparse_conv_set_launch.argtypes = [vp, ip, C.c_int]
     lib.sparse_conv_get_launch.argtypes = [vp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, ip]
@@ -139,6 +141,13 @@ def sparse_conv_forward(handle: int, input_ptr: int, output_ptr: int, N: int, H:
     """Enqueue the convolution of DEVICE input [N][C][H][W] into DEVICE output [N][K][E][F]."""
     _check(_lib.sparse_conv_forward(handle, input_ptr, output_ptr, N, H, W, stride, pad, stream or None),
            "sparse_conv_forward", handle)
+
+
+def sparse_conv_forward_static(handle: int, input_ptr: int, output_ptr: int, N: int, H: int, W: int,
+                               stride: int, pad: int, stream: int = 0) -> None:
+    """sparse_conv_forward without any device allocation: the layer's tables go through the GPU's static scratch."""
+    _check(_lib.sparse_conv_forward_static(handle, input_ptr, output_ptr, N, H, W, stride, pad, stream or None),
+           "sparse_conv_forward_static", handle)
 
 
 def sparse_conv_get_csr(handle: int, dtype: int):
@@ -279,6 +288,12 @@ class SparseConv:
         """x: contiguous CUDA tensor [N][C][H][W] of the layer's dtype; returns [N][K][E][F]."""
         out, geom, stream = self._buffers(x, stride, pad, out)
         sparse_conv_forward(self.handle, x.data_ptr(), out.data_ptr(), *geom, stream)
+        return out
+
+    def forward_static(self, x, stride: int = 1, pad: int = 0, out=None):
+        """forward for callers that cannot allocate device memory (`out` should then be given)."""
+        out, geom, stream = self._buffers(x, stride, pad, out)
+        sparse_conv_forward_static(self.handle, x.data_ptr(), out.data_ptr(), *geom, stream)
         return out
 
     def close(self):

@@ -2,6 +2,8 @@
 #include <hip/hip_runtime_api.h>
 
 #include <algorithm>
+#include <atomic>
+#include <mutex>
 #include <cstdint>
 #include <cstring>
 #include <new>
@@ -19,6 +21,8 @@ extern "C" void sparse_conv_debug_phase_buffer(void* device_buffer)
     g_phase_buffer = static_cast<unsigned long long*>(device_buffer);
 }
 #endif
+
+static_assert(sc::kStaticScratchBytes == SC_STATIC_SCRATCH_BYTES, "the header states the size of the static scratch");
 
 namespace sc {
 
@@ -49,6 +53,8 @@ int get_plan(sparse_conv_s* h, const Geometry& g, Plan** out)
         const Launch& use = tuned != h->tuned.end() ? tuned->second : h->over;
         int rc = build_plan(h->csr, h->C, h->R, h->S, h->dtype == SC_F16 ? 2 : 4, g, use, *p);
         if (rc != SC_OK) return rc;
+        static std::atomic<unsigned long long> next_id{1};
+        p->id = next_id.fetch_add(1, std::memory_order_relaxed);
         it = h->plans.emplace(g, std::move(p)).first;
     }
     *out = it->second.get();
@@ -100,6 +106,143 @@ int upload(sparse_conv_s* h, const std::vector<T>& v, void** dst)
     }
     *dst = d;
     return SC_OK;
+}
+
+// The entry table as the device reads it: per batch the weights, then the offsets two to a word.
+void build_image(Plan& p)
+{
+    if (!p.image.empty() || p.entries.empty()) return;
+    p.image.resize(p.entries.size() / kBatch);
+    for (size_t b = 0; b < p.image.size(); ++b)
+        for (int u = 0; u < kBatch; ++u) {
+            const Entry& en = p.entries[b * kBatch + u];
+            p.image[b].w[u] = en.wbits;
+            const unsigned long long o = (unsigned long long)(uint32_t)en.off << (32 * (u & 1));
+            p.image[b].off2[u / 2] = (u & 1) ? (p.image[b].off2[u / 2] | o) : o;
+        }
+}
+
+void fill_args(const sparse_conv_s* h, const Plan* p, const void* input, void* output, int N, int H, int W,
+               int stride, int pad, KernelArgs& a)
+{
+    a.x = input;
+    a.y = output;
+    a.bias = h->d_bias;
+    a.relu = (h->epilogue & SC_EPILOGUE_RELU) ? 1 : 0;
+    a.nt_store = p->store == 2 ? 1 : 0;
+    a.N = N; a.C = h->C; a.H = H; a.W = W; a.K = h->K; a.E = p->E; a.F = p->F;
+    a.stride = stride; a.pad = pad;
+    a.WP = p->WP; a.WK = p->WK; a.Cc = p->Cc;
+    a.Wp = p->Wp; a.Hs = p->Hs; a.Hb = p->Hb; a.CS = p->CS; a.span = p->span;
+    a.nchunks = p->nchunks; a.ngroups = p->ngroups; a.ntiles = p->ntiles; a.kblocks = p->kblocks;
+    a.tile_elems = p->Cc * p->CS + 1;
+    a.SL = p->SL; a.rows_mode = p->rows_mode; a.tbl_off = p->tbl_off;
+    a.SG = p->SG; a.SP = p->SP;
+    a.nbuf = p->nbuf;
+    a.npass = (int)(((long long)p->SG * p->Cc * p->SP + (long long)kStage * p->threads - 1) /
+                    ((long long)kStage * p->threads));
+    {
+        const long long CP = (long long)p->Cc * p->SP;   // < 2^31: Cc * SP elements fit in LDS
+        a.st_dg = (int)(p->threads / CP);
+        const int r = (int)(p->threads % CP);
+        a.st_dc = r / p->SP;
+        a.st_dp = r % p->SP;
+        a.fd_CP = make_fastdiv((int)CP);
+    }
+    a.fd_Wp = make_fastdiv(p->Wp);
+    a.fd_Hs = make_fastdiv(p->Hs);
+    a.fd_W = make_fastdiv(W);
+    a.fd_HW = make_fastdiv(H * W);
+    a.fd_SP = make_fastdiv(p->SP);
+    a.pitch = p->pitch;
+    a.fd_pitch = make_fastdiv(p->pitch);
+#ifdef SC_PHASE_TIMING
+    a.phase = g_phase_buffer;
+#endif
+}
+
+// What the static device scratch of each GPU currently holds (the id of a plan whose tables were
+// copied there last, 0: nothing usable), and the lock that orders calls of the static entry point.
+std::mutex g_static_lock;
+unsigned long long g_static_holds[64] = {};
+
+size_t round256(size_t n) { return (n + 255) / 256 * 256; }
+
+// Both forward entry points.  use_static: the plan's tables are read from the GPU's static
+// scratch array (copied there by this call unless the previous call left them) instead of from
+// buffers allocated for the plan, and no device memory is allocated.
+int forward_impl(sparse_conv_s* h, const void* input, void* output, int N, int H, int W, int stride, int pad,
+                 void* stream, bool use_static)
+{
+    if (!h || N < 0) return SC_EINVAL;
+    if (!geometry_ok(h, H, W, stride, pad)) return SC_EINVAL;
+    if (N == 0) return SC_OK;
+    if (!input || !output || input == output) return SC_EINVAL;
+    try {
+        Plan* p = nullptr;
+        int rc = get_plan(h, Geometry{N, H, W, stride, pad}, &p);
+        if (rc != SC_OK) return rc;
+        // the kernels index both tensors with 32-bit element offsets
+        if ((long long)N * h->C * H * W >= (1ll << 31) || (long long)N * h->K * p->E * p->F >= (1ll << 31))
+            return SC_EUNSUPPORTED;
+        if (buffers_overlap(h, input, output, N, H, W, stride, pad)) return SC_EINVAL;
+        if ((rc = bind_device(h)) != SC_OK) return rc;
+        KernelArgs a;
+        fill_args(h, p, input, output, N, H, W, stride, pad, a);
+        if (!use_static) {
+            if (!p->uploaded) {
+                build_image(*p);
+                if ((rc = upload(h, p->image, &p->d_entries)) != SC_OK) return rc;
+                if ((rc = upload(h, p->seg, &p->d_seg)) != SC_OK) return rc;
+                if ((rc = upload(h, p->krow, &p->d_krow)) != SC_OK) return rc;
+                p->uploaded = true;
+            }
+            a.entries = static_cast<const uint32_t*>(p->d_entries);
+            a.seg = static_cast<const int*>(p->d_seg);
+            a.krow = static_cast<const int*>(p->d_krow);
+        } else {
+            build_image(*p);
+            const size_t b_entries = p->image.size() * sizeof(Batch), b_seg = p->seg.size() * sizeof(int),
+                         b_krow = p->krow.size() * sizeof(int);
+            const size_t at_seg = round256(b_entries), at_krow = at_seg + round256(b_seg);
+            if (at_krow + round256(b_krow) > kStaticScratchBytes) return SC_ETOOBIG;
+            void* base = nullptr;
+            int e = static_scratch(&base);
+            if (e != 0) {
+                h->last_hip = e;
+                return SC_EHIP;
+            }
+            unsigned char* d = static_cast<unsigned char*>(base);
+            std::lock_guard<std::mutex> hold(g_static_lock);
+            unsigned long long& holds = g_static_holds[h->device & 63];
+            if (holds != p->id) {
+                holds = 0;
+                hipStream_t s = static_cast<hipStream_t>(stream);
+                hipError_t he = hipMemcpyAsync(d, p->image.data(), b_entries, hipMemcpyHostToDevice, s);
+                if (he == hipSuccess) he = hipMemcpyAsync(d + at_seg, p->seg.data(), b_seg, hipMemcpyHostToDevice, s);
+                if (he == hipSuccess) he = hipMemcpyAsync(d + at_krow, p->krow.data(), b_krow, hipMemcpyHostToDevice, s);
+                if (he != hipSuccess) {
+                    h->last_hip = (int)he;
+                    return SC_EHIP;
+                }
+                holds = p->id;
+            }
+            a.entries = reinterpret_cast<const uint32_t*>(d);
+            a.seg = reinterpret_cast<const int*>(d + at_seg);
+            a.krow = reinterpret_cast<const int*>(d + at_krow);
+        }
+        const int e = launch_tile_kernel(h->dtype, p->V, p->KW, p->LP, a, p->grid, p->threads, p->lds_bytes, stream);
+        if (e != 0) {
+            h->last_hip = e;
+            if (use_static) g_static_holds[h->device & 63] = 0;
+            return SC_EHIP;
+        }
+        return SC_OK;
+    } catch (const std::bad_alloc&) {
+        return SC_ENOMEM;
+    } catch (...) {
+        return SC_EHIP;
+    }
 }
 
 }  // namespace
@@ -250,84 +393,13 @@ int sparse_conv_get_launch(sparse_conv_t h, int N, int H, int W, int stride, int
 int sparse_conv_forward(sparse_conv_t h, const void* input, void* output,
                         int N, int H, int W, int stride, int pad, void* stream)
 {
-    if (!h || N < 0) return SC_EINVAL;
-    if (!sc::geometry_ok(h, H, W, stride, pad)) return SC_EINVAL;
-    if (N == 0) return SC_OK;
-    if (!input || !output || input == output) return SC_EINVAL;
-    try {
-        sc::Plan* p = nullptr;
-        int rc = sc::get_plan(h, sc::Geometry{N, H, W, stride, pad}, &p);
-        if (rc != SC_OK) return rc;
-        // the kernels index both tensors with 32-bit element offsets
-        if ((long long)N * h->C * H * W >= (1ll << 31) || (long long)N * h->K * p->E * p->F >= (1ll << 31))
-            return SC_EUNSUPPORTED;
-        if (sc::buffers_overlap(h, input, output, N, H, W, stride, pad)) return SC_EINVAL;
-        if ((rc = sc::bind_device(h)) != SC_OK) return rc;
-        if (!p->uploaded) {
-            {   // device image of the entry table: per batch the weights, then the offsets
-                std::vector<sc::Batch> image(p->entries.size() / sc::kBatch);
-                for (size_t b = 0; b < image.size(); ++b)
-                    for (int u = 0; u < sc::kBatch; ++u) {
-                        const sc::Entry& en = p->entries[b * sc::kBatch + u];
-                        image[b].w[u] = en.wbits;
-                        const unsigned long long o = (unsigned long long)(uint32_t)en.off << (32 * (u & 1));
-                        image[b].off2[u / 2] = (u & 1) ? (image[b].off2[u / 2] | o) : o;
-                    }
-                if ((rc = sc::upload(h, image, &p->d_entries)) != SC_OK) return rc;
-            }
-            if ((rc = sc::upload(h, p->seg, &p->d_seg)) != SC_OK) return rc;
-            if ((rc = sc::upload(h, p->krow, &p->d_krow)) != SC_OK) return rc;
-            p->uploaded = true;
-        }
-        sc::KernelArgs a;
-        a.x = input;
-        a.y = output;
-        a.entries = static_cast<const uint32_t*>(p->d_entries);
-        a.seg = static_cast<const int*>(p->d_seg);
-        a.krow = static_cast<const int*>(p->d_krow);
-        a.bias = h->d_bias;
-        a.relu = (h->epilogue & SC_EPILOGUE_RELU) ? 1 : 0;
-        a.nt_store = p->store == 2 ? 1 : 0;
-        a.N = N; a.C = h->C; a.H = H; a.W = W; a.K = h->K; a.E = p->E; a.F = p->F;
-        a.stride = stride; a.pad = pad;
-        a.WP = p->WP; a.WK = p->WK; a.Cc = p->Cc;
-        a.Wp = p->Wp; a.Hs = p->Hs; a.Hb = p->Hb; a.CS = p->CS; a.span = p->span;
-        a.nchunks = p->nchunks; a.ngroups = p->ngroups; a.ntiles = p->ntiles; a.kblocks = p->kblocks;
-        a.tile_elems = p->Cc * p->CS + 1;
-        a.SL = p->SL; a.rows_mode = p->rows_mode; a.tbl_off = p->tbl_off;
-        a.SG = p->SG; a.SP = p->SP;
-        a.nbuf = p->nbuf;
-        a.npass = (int)(((long long)p->SG * p->Cc * p->SP + (long long)sc::kStage * p->threads - 1) /
-                        ((long long)sc::kStage * p->threads));
-        {
-            const long long CP = (long long)p->Cc * p->SP;   // < 2^31: Cc * SP elements fit in LDS
-            a.st_dg = (int)(p->threads / CP);
-            const int r = (int)(p->threads % CP);
-            a.st_dc = r / p->SP;
-            a.st_dp = r % p->SP;
-            a.fd_CP = sc::make_fastdiv((int)CP);
-        }
-        a.fd_Wp = sc::make_fastdiv(p->Wp);
-        a.fd_Hs = sc::make_fastdiv(p->Hs);
-        a.fd_W = sc::make_fastdiv(W);
-        a.fd_HW = sc::make_fastdiv(H * W);
-        a.fd_SP = sc::make_fastdiv(p->SP);
-        a.pitch = p->pitch;
-        a.fd_pitch = sc::make_fastdiv(p->pitch);
-#ifdef SC_PHASE_TIMING
-        a.phase = g_phase_buffer;
-#endif
-        const int e = sc::launch_tile_kernel(h->dtype, p->V, p->KW, p->LP, a, p->grid, p->threads, p->lds_bytes, stream);
-        if (e != 0) {
-            h->last_hip = e;
-            return SC_EHIP;
-        }
-        return SC_OK;
-    } catch (const std::bad_alloc&) {
-        return SC_ENOMEM;
-    } catch (...) {
-        return SC_EHIP;
-    }
+    return sc::forward_impl(h, input, output, N, H, W, stride, pad, stream, false);
+}
+
+int sparse_conv_forward_static(sparse_conv_t h, const void* input, void* output,
+                               int N, int H, int W, int stride, int pad, void* stream)
+{
+    return sc::forward_impl(h, input, output, N, H, W, stride, pad, stream, true);
 }
 
 int sparse_conv_autotune(sparse_conv_t h, const void* input, void* output,
@@ -497,6 +569,7 @@ const char* sparse_conv_strerror(int code)
         case SC_EUNSUPPORTED: return "configuration not supported by this build";
         case SC_ENOMEM: return "out of memory";
         case SC_EHIP: return "HIP runtime error";
+        case SC_ETOOBIG: return "the layer's tables exceed the static device scratch";
     }
     return "unknown status";
 }

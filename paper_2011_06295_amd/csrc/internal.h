@@ -121,6 +121,8 @@ struct Plan {
     std::vector<int> seg;         // [kblocks][nchunks][WK][1 + KW] = first entry, batches of each row; then one
                                   // terminal descriptor whose first entry is the end of the last segment
     std::vector<int> krow;        // [kblocks][WK][KW] output channel or -1
+    std::vector<Batch> image;     // the entry table as the device reads it (built with the first upload)
+    unsigned long long id = 0;    // unique per built plan (names what the static device scratch currently holds)
     // device copies (owned)
     void* d_entries = nullptr;
     void* d_seg = nullptr;
@@ -176,6 +178,11 @@ struct KernelArgs {
     unsigned long long* phase;  // 8 counters per workgroup, or null
 #endif
 };
+
+// Size of the static device array behind sparse_conv_forward_static, and its address on the current
+// device (looked up once per device).  Returns a hipError_t value (0 = success).
+constexpr size_t kStaticScratchBytes = 16u << 20;   // SC_STATIC_SCRATCH_BYTES of the public header
+int static_scratch(void** ptr);
 
 // Enqueues the tile kernel.  Returns a hipError_t value (0 = success).
 int launch_tile_kernel(int dtype, int V, int KW, int LP, const KernelArgs& a, int grid, int threads,

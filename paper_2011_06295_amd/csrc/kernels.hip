@@ -28,6 +28,7 @@
 #include <hip/hip_runtime.h>
 
 #include <atomic>
+#include <mutex>
 
 #include "internal.h"
 
@@ -612,6 +613,32 @@ int launch_kw(int KW, int LP, const KernelArgs& a, int grid, int threads, int ld
 }
 
 }  // namespace
+
+// Device memory for callers that must not allocate (sparse_conv_forward_static): one array per GPU,
+// part of the loaded code object, held until the process ends.  In host code the array's name is
+// only a handle for hipGetSymbolAddress; its device address differs from GPU to GPU and is looked
+// up once per device, with that device current.
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+int static_scratch(void** ptr)
+{
+    static std::mutex lock;
+    static void* address_on[64] = {};   // per device ordinal
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return (int)e;
+    if (dev < 0 || dev >= 64) return (int)hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> hold(lock);
+    if (!address_on[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return (int)e;
+        if (!p) return (int)hipErrorInvalidSymbol;
+        address_on[dev] = p;
+    }
+    *ptr = address_on[dev];
+    return 0;
+}
 
 int launch_tile_kernel(int dtype, int V, int KW, int LP, const KernelArgs& a, int grid, int threads,
                        int lds_bytes, void* stream)
