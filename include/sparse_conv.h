@@ -171,7 +171,7 @@ int sparse_conv_get_codebook(sparse_conv_t h, const unsigned char** codes, const
 /*
  * sparse_conv_set_launch - override the per-layer launch configuration, this
  * library's counterpart of the per-layer thread-block count the paper tunes
- * (section 8, subBatchSize; section 9).  params[0..nparams) are, in order:
+ * (section 8, subBatchSize; section 9).  params[0..nparams), nparams <= 10, are, in order:
  *   [0] V   images interleaved per LDS element (1, 2, 4 or 8; 0 = automatic)
  *   [1] WP  wavefronts across output positions (64 * LP positions each) per workgroup
  *   [2] WK  wavefronts across output channels per workgroup (WP*WK <= 16)
@@ -186,6 +186,11 @@ int sparse_conv_get_codebook(sparse_conv_t h, const unsigned char** codes, const
  *           lines the other workgroups of the launch still read their input from;
  *           faster for some layers, slower for others: sparse_conv_autotune
  *           measures both); automatic without a measurement is 1
+ *   [9] what a lane stands for: 1 a position of the zero-padded input lattice (positions on
+ *           padding compute a value that is never stored); 1 + G with G = 1, 2, 4, 8 or 16: an
+ *           output element, with G groups of V images interleaved element by element in the
+ *           tile (no lane is spent on padding; needs LP = 1).  Which is faster depends on the
+ *           map size; sparse_conv_autotune measures both kinds.
  * Missing trailing entries and zeros mean "automatic".  nparams = 0 restores
  * the automatic choice.  Cached plans are discarded.  SC_EINVAL for values the
  * kernels cannot run; a configuration that cannot fit is reported by forward.
@@ -216,7 +221,8 @@ int sparse_conv_autotune(sparse_conv_t h, const void* input, void* output,
  * sparse_conv_rank_launches - the candidates sparse_conv_autotune would time, for callers
  * that measure in their own setting (inside a pass through a network, say): up to
  * max_candidates launch configurations for the geometry, cheapest cost estimate first,
- * within whatever sparse_conv_set_launch has pinned.  params receives 9 ints per
+ * within whatever sparse_conv_set_launch has pinned (the list goes round the kinds of
+ * lanes: the best of each kind, then the second best of each, ...).  params receives 10 ints per
  * candidate, in the order sparse_conv_set_launch takes them (each can be passed back to
  * it as it is); *count the number written.  Needs no GPU.
  */
@@ -249,8 +255,9 @@ int sparse_conv_check_plan(sparse_conv_t h, int N, int H, int W, int stride, int
  * budget in force, [6] workgroups launched, [7] LDS bytes
  * per workgroup, [8] threads per workgroup, [9] stored plan entries
  * (including batch padding), [10] LP, [11] channel blocks, [12] kind of output store
- * (1 or 2).  [0..5] are in the order of sparse_conv_set_launch.  Builds the plan's
- * host side if needed; needs no GPU.  params must have room for 13 ints. */
+ * (1 or 2), [13] what a lane stands for (1, or 1 + G, as sparse_conv_set_launch takes it),
+ * [14], [15] reserved (0).  [0..5] are in the order of sparse_conv_set_launch.  Builds the plan's
+ * host side if needed; needs no GPU.  params must have room for 16 ints. */
 int sparse_conv_get_launch(sparse_conv_t h, int N, int H, int W, int stride, int pad, int* params);
 
 /* HIP error code of the last failing runtime call made through this handle (0 if none). */

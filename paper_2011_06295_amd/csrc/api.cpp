@@ -156,6 +156,14 @@ void fill_args(const sparse_conv_s* h, const Plan* p, const void* input, void* o
     a.fd_SP = make_fastdiv(p->SP);
     a.pitch = p->pitch;
     a.fd_pitch = make_fastdiv(p->pitch);
+    a.real = p->G ? 1 : 0;
+    a.logG = 0;
+    while ((1 << a.logG) < p->G) ++a.logG;
+    a.PT = p->PT;
+    a.nout = p->G ? (int)(p->npos / p->G) : 0;
+    a.fd_EF = make_fastdiv(p->E * p->F);
+    a.fd_F = make_fastdiv(p->F);
+    a.fd_GW = make_fastdiv((p->G ? p->G : 1) * W);
 #ifdef SC_PHASE_TIMING
     a.phase = g_phase_buffer;
 #endif
@@ -332,8 +340,8 @@ int sparse_conv_get_csr(sparse_conv_t h, int* K, long long* nnz,
 
 int sparse_conv_set_launch(sparse_conv_t h, const int* params, int nparams)
 {
-    if (!h || nparams < 0 || nparams > 9 || (nparams > 0 && !params)) return SC_EINVAL;
-    int v[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};
+    if (!h || nparams < 0 || nparams > 10 || (nparams > 0 && !params)) return SC_EINVAL;
+    int v[10] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
     for (int i = 0; i < nparams; ++i) {
         if (params[i] < 0) return SC_EINVAL;
         v[i] = params[i];
@@ -344,8 +352,11 @@ int sparse_conv_set_launch(sparse_conv_t h, const int* params, int nparams)
     if (v[1] > 16 || v[2] > 16 || v[1] * (v[2] ? v[2] : 1) > 16) return SC_EINVAL;
     if (v[5] > 160 * 1024) return SC_EINVAL;
     if (v[6] > 2 || v[8] > 2) return SC_EINVAL;
+    if (v[9] > 17 || (v[9] > 1 && ((v[9] - 1) & (v[9] - 2)))) return SC_EINVAL;   // 0, 1, or 1 + a power of two up to 16
+    if (v[9] > 1 && v[6] == 2) return SC_EINVAL;                                   // output lanes: one output per lane
     sc::Launch l;
     l.V = v[0]; l.WP = v[1]; l.WK = v[2]; l.KW = v[3]; l.Cc = v[4]; l.lds_budget = v[5]; l.LP = v[6]; l.kblocks = v[7]; l.store = v[8];
+    l.lanes = v[9];
     h->over = l;
     h->plans.clear();
     h->tuned.clear();
@@ -381,8 +392,9 @@ int sparse_conv_get_launch(sparse_conv_t h, int N, int H, int W, int stride, int
         sc::Plan* p = nullptr;
         int rc = sc::get_plan(h, sc::Geometry{N, H, W, stride, pad}, &p);
         if (rc != SC_OK) return rc;
-        const int v[13] = {p->V, p->WP, p->WK, p->KW, p->Cc, h->over.lds_budget,
-                           p->grid, p->lds_bytes, p->threads, (int)p->entries.size(), p->LP, p->kblocks, p->store};
+        const int v[16] = {p->V, p->WP, p->WK, p->KW, p->Cc, h->over.lds_budget,
+                           p->grid, p->lds_bytes, p->threads, (int)p->entries.size(), p->LP, p->kblocks, p->store,
+                           1 + p->G, 0, 0};
         std::memcpy(params, v, sizeof(v));
         return SC_OK;
     } catch (...) {
@@ -533,8 +545,8 @@ int sparse_conv_rank_launches(sparse_conv_t h, int N, int H, int W, int stride, 
         const int n = (int)std::min<size_t>(ranked.size(), (size_t)max_candidates);
         for (int i = 0; i < n; ++i) {
             const sc::Launch& l = ranked[i].second;
-            const int v[9] = {l.V, l.WP, l.WK, l.KW, l.Cc, 0, l.LP, l.kblocks, l.store ? l.store : 1};
-            std::memcpy(params + 9 * i, v, sizeof(v));
+            const int v[10] = {l.V, l.WP, l.WK, l.KW, l.Cc, 0, l.LP, l.kblocks, l.store ? l.store : 1, l.lanes};
+            std::memcpy(params + 10 * i, v, sizeof(v));
         }
         *count = n;
         return SC_OK;

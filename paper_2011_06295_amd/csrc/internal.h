@@ -53,6 +53,8 @@ struct Launch {
     int LP = 0;   // positions per lane (1 or 2)
     int kblocks = 0;  // channel blocks (at least ceil(K / (WK * KW)); more leaves slots empty)
     int store = 0;    // output stores: 1 ordinary, 2 non-temporal (the output is not read again by this kernel)
+    int lanes = 0;    // what a lane stands for: 1 a lattice position, 1 + G (G = 1, 2, 4, 8, 16) an output element, with
+                      // G image groups interleaved element by element (see Plan)
 };
 
 struct Geometry {
@@ -93,10 +95,20 @@ static_assert(sizeof(Batch) == kBatch * sizeof(Entry), "same bytes as the entrie
 // that lattice stands for the output whose receptive field starts there; tap
 // (r, s) of it is the element at q + r*Wp + s, so neighbouring lanes always
 // read neighbouring LDS elements, whatever the tap.
+//
+// Lanes stand either for lattice positions (64 * LP consecutive ones a wavefront; positions on padding
+// compute a value nobody stores), or for output elements only (G > 0): G consecutive image groups form a
+// super-group whose lattice is interleaved element by element, element index ((Y*Wp + X)*G + g); the
+// outputs of the batch are numbered (super-group, i, j), a tile owns span / G consecutive ones, and lane
+// l of a wavefront is image group l % G of the wavefront's output l / G.  Sixteen consecutive lanes then
+// still read sixteen consecutive 16-byte elements (16 / G outputs of one row x G groups), which is what
+// keeps ds_read_b128 free of bank conflicts, and no lane is spent on padding.
 struct Plan {
     int V, WP, WK, KW, Cc, LP;
+    int G;         // 0: lanes are lattice positions; else image groups interleaved per element, lanes are outputs
+    int PT;        // G > 0: outputs per tile (span / G)
     int store;     // 1 ordinary output stores, 2 non-temporal
-    int E, F;
+    int E, F, st;  // output size, stride
     int Wp;        // row pitch of the padded lattice
     int Hs;        // rows per image group
     int span;      // positions per workgroup = 64 * WP
@@ -173,7 +185,12 @@ struct KernelArgs {
     int st_dg, st_dc, st_dp; // nthreads = st_dg * (Cc * SP) + st_dc * SP + st_dp
     int nbuf;                // tile buffers in LDS: 2 when there are several chunks
     int npass;               // staging passes per chunk: ceil(SG * Cc * SP / (kStage * threads))
+    int real;                // lanes are output elements (else lattice positions)
+    int logG;                // log2 of the image groups interleaved per element (0 unless real)
+    int PT;                  // real: outputs per tile
+    int nout;                // real: outputs of the whole batch = super-groups * E * F
     FastDiv fd_Wp, fd_Hs, fd_W, fd_HW, fd_SP, fd_CP, fd_pitch;  // divisors Wp, Hs, W, H*W, SP, Cc*SP, pitch
+    FastDiv fd_EF, fd_F, fd_GW;                                 // real: divisors E*F, F, G*W
 #ifdef SC_PHASE_TIMING
     unsigned long long* phase;  // 8 counters per workgroup, or null
 #endif

@@ -170,16 +170,36 @@ __global__ __launch_bounds__(1024) void tile_kernel(const KernelArgs a)
     const int wp = wave % a.WP;
     const int wk = wave / a.WP;
 
-    // The tile covers lattice positions [q0, q0 + span); its row 0 is lattice row Y0.
-    const long long q0 = (long long)tile_id * a.span;
-    const int Y0 = fdiv((int)q0, a.fd_Wp);      // the host guarantees fewer than 2^31 positions
-    const int lq0 = (int)q0 - Y0 * a.Wp;
-
-    // lane -> its LP positions: wavefront wp covers positions [wp*LP*64, (wp+1)*LP*64) of the tile,
-    // the lane's p-th position is 64*p after its first
-    const int lrel = lq0 + wp * (LP * 64) + lane;  // first position, relative to the start of lattice row Y0
-    // tile element of that position: the tile starts at that row, or (banded tile) at the first position
-    const int lpos = a.rows_mode == 2 ? wp * (LP * 64) + lane : lrel;
+    // Lattice lanes: the tile covers lattice positions [q0, q0 + span); its row 0 is lattice row Y0; wavefront wp
+    // covers positions [wp*LP*64, (wp+1)*LP*64) of the tile, the lane's p-th position is 64*p after its first.
+    // Output lanes: the tile covers outputs [o0, o0 + PT) of the numbering (super-group, i, j); its row 0 is the
+    // lattice row of its first output; lane l of wavefront wp is image group l % G of output wp * (64 / G) + l / G.
+    int Y0, g_first, lrel = 0, lpos, my_o = 0;
+    long long q0 = 0;
+    if (a.real) {
+        const int G1 = (1 << a.logG) - 1;
+        const int EF = a.E * a.F;
+        const int o0 = tile_id * a.PT;                   // the host guarantees fewer than 2^31 lanes in all
+        const int u0 = fdiv(o0, a.fd_EF);
+        Y0 = u0 * a.Hs + fdiv(o0 - u0 * EF, a.fd_F) * a.stride;
+        g_first = u0 << a.logG;
+        my_o = o0 + wp * (64 >> a.logG) + (lane >> a.logG);
+        // lanes past the last output work on the last output again (nothing of theirs is stored)
+        const int o = my_o < a.nout ? my_o : a.nout - 1;
+        const int u = fdiv(o, a.fd_EF);
+        const int rem = o - u * EF;
+        const int i = fdiv(rem, a.fd_F);
+        const int j = rem - i * a.F;
+        lpos = (((u * a.Hs + i * a.stride - Y0) * a.Wp + j * a.stride) << a.logG) + (lane & G1);
+    } else {
+        q0 = (long long)tile_id * a.span;
+        Y0 = fdiv((int)q0, a.fd_Wp);      // the host guarantees fewer than 2^31 positions
+        const int lq0 = (int)q0 - Y0 * a.Wp;
+        lrel = lq0 + wp * (LP * 64) + lane;  // first position, relative to the start of lattice row Y0
+        // tile element of that position: the tile starts at that row, or (banded tile) at the first position
+        lpos = a.rows_mode == 2 ? wp * (LP * 64) + lane : lrel;
+        g_first = fdiv(Y0, a.fd_Hs);
+    }
     const int lposb = lpos * (int)sizeof(vec);
 
     float acc[KW][LP][V];
@@ -199,7 +219,6 @@ __global__ __launch_bounds__(1024) void tile_kernel(const KernelArgs a)
     // group of the tile (plus the chunk's first channel) and ends with the
     // input: offsets marked invalid (>= 2^31) and images past the end of the
     // batch are out of its range and read as zero, so no load needs a branch.
-    const int g_first = fdiv(Y0, a.fd_Hs);
     const size_t tile_base = (size_t)g_first * V * img_bytes;
     const size_t total_bytes = (size_t)a.N * img_bytes;
     auto chunk_rsrc = [&](int c0) {
@@ -271,7 +290,7 @@ __global__ __launch_bounds__(1024) void tile_kernel(const KernelArgs a)
     // and staging then only adds channel strides.
     int2* tbl = reinterpret_cast<int2*>(smem + a.tbl_off);
     for (int sl = tid; sl < a.SL; sl += nthreads) {
-        int gs, ys, xx, Yt;
+        int gs, ys, xx, Yt, gsub = 0;
         if (a.rows_mode == 2) {  // banded tile: element sl is lattice element q0 + band * Wp + offset
             const int band = fdiv(sl, a.fd_pitch);
             const int Ls = (int)q0 + band * a.Wp + (sl - band * a.pitch);
@@ -280,26 +299,30 @@ __global__ __launch_bounds__(1024) void tile_kernel(const KernelArgs a)
             ys = Ys - gs * a.Hs - a.pad;
             xx = Ls - Ys * a.Wp - a.pad;
             Yt = 0;
-        } else if (a.rows_mode) {
-            Yt = fdiv(sl, a.fd_W);
-            xx = sl - Yt * a.W;
+        } else if (a.rows_mode) {   // slot = (tile row, image group of the super-group, column)
+            Yt = fdiv(sl, a.fd_GW);
+            const int rem = sl - Yt * (a.W << a.logG);
+            gsub = fdiv(rem, a.fd_W);
+            xx = rem - gsub * a.W;
             const int Ys = Y0 + Yt;
-            gs = fdiv(Ys, a.fd_Hs);
-            ys = Ys - gs * a.Hs - a.pad;
-        } else {
+            const int us = fdiv(Ys, a.fd_Hs);
+            gs = (us << a.logG) + gsub;
+            ys = Ys - us * a.Hs - a.pad;
+        } else {                    // slot = (image group, row, column) of the groups the tile can touch
             const int gi = fdiv(sl, a.fd_HW);
             const int rem = sl - gi * chan_stride;
             ys = fdiv(rem, a.fd_W);
             xx = rem - ys * a.W;
             gs = g_first + gi;
-            Yt = gs * a.Hs + a.pad + ys - Y0;
+            gsub = gs & ((1 << a.logG) - 1);
+            Yt = (gs >> a.logG) * a.Hs + a.pad + ys - Y0;
         }
         const bool ok = gs < a.ngroups && ys >= 0 && ys < a.H && xx >= 0 && xx < a.W && Yt >= 0 && Yt < a.Hb;
         int2 t;
         // (gs - g_first) * V * img_bytes < 2^31 is guaranteed by the host
         t.x = ok ? (int)((unsigned)((gs - g_first) * V) * img_bytes + (unsigned)(ys * a.W + xx) * (unsigned)sizeof(T))
                  : (int)0x80000000;
-        t.y = !ok ? 0 : a.rows_mode == 2 ? sl : Yt * a.Wp + a.pad + xx;
+        t.y = !ok ? 0 : a.rows_mode == 2 ? sl : ((Yt * a.Wp + a.pad + xx) << a.logG) + gsub;
         tbl[sl] = t;
     }
     // A chunk is SG * Cc * SP units, unit u = (slot group * Cc + channel) * SP + slot: in that
@@ -523,16 +546,27 @@ __global__ __launch_bounds__(1024) void tile_kernel(const KernelArgs a)
     const size_t plane = (size_t)a.E * a.F;
 #pragma unroll
     for (int p = 0; p < LP; ++p) {
-        // position -> output element (if any)
-        const int rel = lrel + p * 64;
-        const int Yl = fdiv(rel, a.fd_Wp);
-        const int X = rel - Yl * a.Wp;
-        const int Y = Y0 + Yl;
-        const int g = fdiv(Y, a.fd_Hs);
-        const int yy = Y - g * a.Hs;
-        const int oi = yy / a.stride;
-        const int oj = X / a.stride;
-        const bool valid = g < a.ngroups && oi * a.stride == yy && oj * a.stride == X && oi < a.E && oj < a.F;
+        // lane -> output element (if any) and image group
+        int g, oi, oj;
+        bool valid;
+        if (a.real) {
+            const int u = fdiv(my_o, a.fd_EF);
+            const int rem = my_o - u * (a.E * a.F);
+            oi = fdiv(rem, a.fd_F);
+            oj = rem - oi * a.F;
+            g = (u << a.logG) + (lane & ((1 << a.logG) - 1));
+            valid = my_o < a.nout && g < a.ngroups;
+        } else {
+            const int rel = lrel + p * 64;
+            const int Yl = fdiv(rel, a.fd_Wp);
+            const int X = rel - Yl * a.Wp;
+            const int Y = Y0 + Yl;
+            g = fdiv(Y, a.fd_Hs);
+            const int yy = Y - g * a.Hs;
+            oi = yy / a.stride;
+            oj = X / a.stride;
+            valid = g < a.ngroups && oi * a.stride == yy && oj * a.stride == X && oi < a.E && oj < a.F;
+        }
         if (!valid) continue;
         const size_t pix = (size_t)oi * a.F + oj;
 #pragma unroll

@@ -38,7 +38,8 @@ bool pow2_in(int v, int lo, int hi) { return v >= lo && v <= hi && (v & (v - 1))
 struct Shape {
     int K, C, R, S, ub;  // ub = bytes of one LDS element (V images)
     int V, H, W, Wp, Hs, elem_bytes;
-    long long npos;
+    int G;               // 0: lanes are lattice positions; else image groups interleaved per element (lanes are outputs)
+    long long npos;      // lanes of the whole batch: lattice positions, or outputs * G
     double row_nnz;      // mean stored weights per output channel
 };
 
@@ -46,6 +47,21 @@ struct Cand {
     int V, WP, WK, KW, Cc, LP, kblocks;
     int Hb, CS, lds, SL, rows_mode, SG, nbuf, pitch;
 };
+
+// Output-lane tiles: the most lattice rows between the first and the last of PT consecutive outputs
+// (outputs are numbered super-group, row, column; super-group u starts at lattice row u * Hs).
+// What a tile spans depends only on its first output modulo E*F, which repeats after at most E*F tiles.
+int output_tile_span(long long nout, int PT, int EF, int F, int Hs, int st)
+{
+    const long long ntiles = (nout + PT - 1) / PT;
+    int best = 0;
+    for (long long t = 0; t < std::min<long long>(ntiles, (long long)EF + 1); ++t) {
+        const long long o0 = t * PT, o1 = std::min<long long>(o0 + PT, nout) - 1;
+        const long long Ya = o0 / EF * Hs + o0 % EF / F * st, Yb = o1 / EF * Hs + o1 % EF / F * st;
+        best = std::max(best, (int)(Yb - Ya));
+    }
+    return best;
+}
 
 // Tile height in lattice rows for a window of `span` positions starting anywhere in a row.
 int tile_rows(int span, int Wp, int R, int S) { return (Wp - 1 + span - 1 + (R - 1) * Wp + S - 1) / Wp + 1; }
@@ -148,6 +164,22 @@ double estimate(const Shape& s, const Cand& c)
     return t;
 }
 
+// Output-lane tiles: the most super-groups that have input rows among the Hst lattice rows a tile stages
+// (rows from the tile's first output on; super-group u's input rows start pad rows below u * Hs).
+int output_tile_groups(long long nout, int PT, int EF, int F, int Hs, int st, int Hst, int pad)
+{
+    const long long ntiles = (nout + PT - 1) / PT;
+    int best = 1;
+    for (long long t = 0; t < std::min<long long>(ntiles, (long long)EF + 1); ++t) {
+        const long long o0 = t * PT;
+        const long long Ya = o0 / EF * Hs + o0 % EF / F * st, Yz = Ya + Hst - 1;   // first and last staged row
+        long long ua = Ya / Hs, uz = Yz / Hs;
+        if (uz * Hs + pad > Yz) --uz;                     // only padding rows of the last one
+        best = std::max(best, (int)(uz - ua + 1));
+    }
+    return best;
+}
+
 }  // namespace
 
 // floor(n / d) = (n * mul) >> (32 + shift) for every 0 <= n < 2^31, where
@@ -170,6 +202,7 @@ int build_plan(const Csr& csr, int C, int R, int S, int elem_bytes, const Geomet
     const int st = g.stride, pad = g.pad;
     p.E = (g.H + 2 * pad - R) / st + 1;
     p.F = (g.W + 2 * pad - S) / st + 1;
+    p.st = st;
 
     if (over.lds_budget > kMaxLds) return SC_EINVAL;
     if (over.KW && !pow2_in(over.KW, 1, 16)) return SC_EINVAL;
@@ -178,6 +211,7 @@ int build_plan(const Csr& csr, int C, int R, int S, int elem_bytes, const Geomet
     if (over.V && !pow2_in(over.V, 1, vmax)) return SC_EINVAL;
     if (over.LP && !pow2_in(over.LP, 1, 2)) return SC_EINVAL;
     if (over.store < 0 || over.store > 2) return SC_EINVAL;
+    if (over.lanes < 0 || (over.lanes > 1 && !pow2_in(over.lanes - 1, 1, 16))) return SC_EINVAL;
 
     // ---- candidates
     static const int budgets[] = {160 * 1024, 80 * 1024, 53 * 1024, 40 * 1024, 32 * 1024};
@@ -186,12 +220,43 @@ int build_plan(const Csr& csr, int C, int R, int S, int elem_bytes, const Geomet
     double best_t = -1.0;
     bool too_many_positions = false;
     // images interleaved per LDS element: an element of up to 16 bytes, not wider than the batch can fill
+    const int EF = p.E * p.F;
     for (int V = vmax; V >= 1; V /= 2) {
         if (over.V && V != over.V) continue;
         if (!over.V && V > 1 && V / 2 >= g.N) continue;
+        const int ngroups = std::max(1, cdiv(g.N, V));
+        // What lanes stand for: lattice positions (G = 0), or outputs with G image groups interleaved.  Unasked,
+        // output lanes are tried where ds_read_b128 stays at full rate.  Measured rule: in each half of a
+        // wavefront, lanes l and l + 16 must read elements that are congruent modulo 16, and 16 consecutive
+        // lanes distinct ones; 32 consecutive elements do that whatever their alignment, 16-element runs
+        // only at distances that are multiples of 16 (18: half rate).  So 32 consecutive lanes must be
+        // 32 / G outputs of one row (unit stride) times G groups.  Tried: the smallest such G and twice it
+        // (larger G: more images and fewer rows of the map in a tile).
+        int modes[8], nmodes = 0;
+        if (over.lanes <= 1) modes[nmodes++] = 0;
+        if (over.lanes > 1) {
+            modes[nmodes++] = over.lanes - 1;
+        } else if (over.lanes == 0 && V * elem_bytes == 16) {
+            int taken = 0;
+            for (int G = 1; G <= 16 && taken < 3; G *= 2) {
+                if (st != 1) break;
+                if (G > 1 && G / 2 >= ngroups) break;      // groups the batch cannot fill
+                if (p.F % (32 / G) != 0) {
+                    // 16 lanes are a whole row (or rows): fine if the row distance is a multiple of 16 elements,
+                    // where a wider pitch that makes it one at most doubles it
+                    const int wp0 = std::max(g.W + pad, p.F), unit = 16 / G;
+                    if (p.F % unit != 0 || (wp0 + unit - 1) / unit * unit > wp0 * 2) continue;
+                }
+                modes[nmodes++] = G;
+                ++taken;
+            }
+        }
+        for (int mi = 0; mi < nmodes; ++mi) {
+        const int G = modes[mi];
         Shape s;
         s.K = K; s.C = C; s.R = R; s.S = S;
         s.V = V;
+        s.G = G;
         s.elem_bytes = elem_bytes;
         s.ub = V * elem_bytes;
         s.H = g.H; s.W = g.W;
@@ -199,8 +264,20 @@ int build_plan(const Csr& csr, int C, int R, int S, int elem_bytes, const Geomet
         // next group/row, but every output's receptive field must still start inside its own group
         s.Wp = std::max(g.W + pad, (p.F - 1) * st + 1);
         s.Hs = std::max(g.H + pad, (p.E - 1) * st + 1);
-        const int ngroups = std::max(1, cdiv(g.N, V));
-        s.npos = (long long)ngroups * s.Hs * s.Wp;
+        long long nout = 0;
+        if (G) {
+            // runs of 16 lanes (whole rows) that are not halves of a 32-lane run: the pitch makes the distance
+            // between rows a multiple of 16 elements
+            if (st == 1 && G < 16 && p.F % (32 / G) != 0 && p.F % (16 / G) == 0) s.Wp = (s.Wp + 16 / G - 1) / (16 / G) * (16 / G);
+            nout = (long long)cdiv(ngroups, G) * EF;
+            s.npos = nout * G;
+            if ((long long)cdiv(ngroups, G) * s.Hs * s.Wp * G + (long long)(R + 1) * s.Wp * G + 2048 >= (1ll << 31)) {
+                too_many_positions = true;
+                continue;
+            }
+        } else {
+            s.npos = (long long)ngroups * s.Hs * s.Wp;
+        }
         s.row_nnz = K > 0 ? (double)csr.colidx.size() / K : 0.0;
         if (s.npos + (long long)(R + 1) * s.Wp + 2048 >= (1ll << 31)) {  // lattice elements are 32-bit in the kernel
             too_many_positions = true;
@@ -210,26 +287,38 @@ int build_plan(const Csr& csr, int C, int R, int S, int elem_bytes, const Geomet
         for (int WP = 1; WP <= 8; WP *= 2) {
             if (over.LP && LP != over.LP) break;
             if (over.WP && WP != 1) break;
+            if (G && LP != 1) continue;            // output lanes: one output per lane
             const int wp = over.WP ? over.WP : WP;
             const int span = kWave * wp * LP;
-            const int Hb = tile_rows(span, s.Wp, R, S);
+            const int ge = G ? G : 1;
+            int Hb;
+            if (G) {
+                const int wrap = ((p.F - 1) * st + S - 1) / s.Wp;     // taps of a row's last outputs run into the next row
+                Hb = output_tile_span(nout, span / G, EF, p.F, s.Hs, st) + R + wrap;
+            } else {
+                Hb = tile_rows(span, s.Wp, R, S);
+            }
             // Tile layout per channel.  Contiguous: the Hb lattice rows the positions and their taps
             // touch, pitch Wp.  Banded (maps much wider than the tile): R bands of span + S - 1
             // consecutive lattice elements, band r starting r rows below the first position.
             const int P2 = span + S - 1;
-            const bool banded = (long long)R * P2 < (long long)Hb * s.Wp;
-            const long long CS = banded ? (long long)R * P2 : (long long)Hb * s.Wp;
+            const bool banded = !G && (long long)R * P2 < (long long)Hb * s.Wp;
+            const long long CS = banded ? (long long)R * P2 : (long long)Hb * s.Wp * ge;
             const int pitch = banded ? P2 : s.Wp;
             // staging slots per channel: every tile element (banded), the tile's rows, or (small maps)
             // the whole planes of every group it can touch
             // (whole planes only where a plane is a short run of memory: the order then continues across channels)
-            const int rows_spanned = banded ? (R - 1) + (P2 + s.Wp - 1) / s.Wp + 1 : Hb;
-            const long long GC = (rows_spanned + s.Hs - 2) / s.Hs + 1;      // image groups a tile can touch
+            // (output lanes: the row that only the wrap of a row's last taps reaches holds padding there, it is not staged)
+            const int Hst = G ? Hb - ((p.F - 1) * st + S - 1) / s.Wp : Hb;
+            const int rows_spanned = banded ? (R - 1) + (P2 + s.Wp - 1) / s.Wp + 1 : Hst;
+            long long GC = ((rows_spanned + s.Hs - 2) / s.Hs + 1) * (long long)ge;   // image groups a tile can touch
+            if (G) GC = (long long)output_tile_groups(nout, span / G, EF, p.F, s.Hs, st, Hst, pad) * G;
             const bool rows_mode = banded || s.Hs >= Hb || (long long)g.H * g.W * elem_bytes >= 128;
-            const long long SL = banded ? CS : rows_mode ? (long long)Hb * g.W : GC * g.H * g.W;
+            const long long SL = banded ? CS : rows_mode ? (long long)Hst * ge * g.W : GC * g.H * g.W;
             const long long tbl = SL * 8;
             // slot offsets are 31-bit byte offsets from the first image group of a tile
             if (GC * V * C * g.H * g.W * elem_bytes >= (1ll << 31)) continue;
+            if (CS >= (1ll << 24) || SL >= (1ll << 24)) continue;
             for (int WK = 1; WK <= kMaxWaves; ++WK) {
                 if (over.WK && WK != 1) break;
                 const int wk = over.WK ? over.WK : WK;
@@ -279,6 +368,7 @@ int build_plan(const Csr& csr, int C, int R, int S, int elem_bytes, const Geomet
                                 Launch l;
                                 l.V = V; l.WP = wp; l.WK = wk; l.KW = kw; l.Cc = Cc; l.LP = LP; l.kblocks = kblocks;
                                 l.store = over.store;
+                                l.lanes = 1 + G;
                                 ranked->emplace_back(t, l);
                             }
                             if (best_t < 0 || t < best_t) {
@@ -291,6 +381,7 @@ int build_plan(const Csr& csr, int C, int R, int S, int elem_bytes, const Geomet
                 }
             }
         }
+        }
     }
     if (best_t < 0 && too_many_positions) return SC_EUNSUPPORTED;
     if (best_t < 0) return SC_EUNSUPPORTED;
@@ -302,9 +393,28 @@ int build_plan(const Csr& csr, int C, int R, int S, int elem_bytes, const Geomet
             bool seen = false;
             for (const auto& u : uniq)
                 seen = seen || (u.second.V == e.second.V && u.second.WP == e.second.WP && u.second.WK == e.second.WK &&
-                                u.second.KW == e.second.KW && u.second.Cc == e.second.Cc && u.second.LP == e.second.LP && u.second.kblocks == e.second.kblocks);
+                                u.second.KW == e.second.KW && u.second.Cc == e.second.Cc && u.second.LP == e.second.LP &&
+                                u.second.kblocks == e.second.kblocks && u.second.lanes == e.second.lanes);
             if (!seen) uniq.push_back(e);
-            if (uniq.size() >= 64) break;
+            if (uniq.size() >= 256) break;
+        }
+        // The estimate was fitted on lattice lanes and ranks the kinds of lanes against each other only roughly: the
+        // list goes round the kinds (best of each, second best of each, ...) so that a measurement of the first few
+        // sees every kind.
+        {
+            std::vector<std::pair<double, Launch>> mixed;
+            std::vector<char> used(uniq.size(), 0);
+            while (mixed.size() < uniq.size() && mixed.size() < 64) {
+                bool took[18] = {};
+                for (size_t i = 0; i < uniq.size() && mixed.size() < 64; ++i) {
+                    const int kind = uniq[i].second.lanes;
+                    if (used[i] || took[kind]) continue;
+                    took[kind] = true;
+                    used[i] = 1;
+                    mixed.push_back(uniq[i]);
+                }
+            }
+            uniq.swap(mixed);
         }
         ranked->swap(uniq);
         return SC_OK;
@@ -317,6 +427,8 @@ int build_plan(const Csr& csr, int C, int R, int S, int elem_bytes, const Geomet
     p.store = over.store ? over.store : 1;   // which kind is faster depends on what else lives in L2: only a measurement tells
     p.Wp = s.Wp; p.Hs = s.Hs;
     p.span = kWave * p.WP * p.LP;
+    p.G = s.G;
+    p.PT = s.G ? p.span / s.G : 0;
     p.Hb = best.Hb; p.CS = best.CS;
     p.nchunks = cdiv(C, p.Cc);
     p.ngroups = ngroups;
@@ -398,6 +510,7 @@ int build_plan(const Csr& csr, int C, int R, int S, int elem_bytes, const Geomet
         }
     }
 
+    const int ge = p.G ? p.G : 1;   // elements per lattice position
     const int SW = p.KW + 1;  // descriptor: first entry, then batches of each of the KW rows
     p.seg.assign(((size_t)p.kblocks * nchunks * p.WK + 1) * SW, 0);   // one terminal descriptor
     p.entries.clear();
@@ -424,7 +537,7 @@ int build_plan(const Csr& csr, int C, int R, int S, int elem_bytes, const Geomet
                         const float wv = csr.val32[(size_t)(q - csr.colidx.data())];
                         uint32_t wb;
                         __builtin_memcpy(&wb, &wv, 4);
-                        last = Entry{wb, ((c - c0) * p.CS + r * p.pitch + sx) * s.ub};
+                        last = Entry{wb, ((c - c0) * p.CS + (r * p.pitch + sx) * ge) * s.ub};
                         p.entries.push_back(last);
                     }
                     const int nb = cdiv(n, kBatch);
@@ -466,7 +579,21 @@ int check_plan(const Csr& csr, int C, int R, int S, int elem_bytes, const Plan& 
     // 3-6: the segments, in the order the kernel walks them
     if (p.seg.size() != ((size_t)p.kblocks * p.nchunks * p.WK + 1) * SW) return 3;
     const bool banded = p.rows_mode == 2;
-    const long long lane_reach = banded ? p.span - 1 : (long long)p.Wp - 1 + p.span - 1;   // furthest position of a lane
+    const int ge = p.G ? p.G : 1;
+    if (p.G && (p.LP != 1 || p.PT * p.G != p.span || banded)) return 1;
+    // furthest tile element under a lane
+    long long lane_reach = banded ? p.span - 1 : (long long)p.Wp - 1 + p.span - 1;
+    if (p.G) {
+        const int wrap = ((p.F - 1) * p.st + S - 1) / p.Wp;
+        lane_reach = ((long long)(p.Hb - R - wrap) * p.Wp + (long long)(p.F - 1) * p.st) * p.G + p.G - 1;
+        // the rows a tile's outputs span, worked out again
+        const long long EF = (long long)p.E * p.F, nout = p.npos / p.G;
+        for (long long t = 0; t < p.ntiles; ++t) {
+            const long long o0 = t * p.PT, o1 = std::min<long long>(o0 + p.PT, nout) - 1;
+            const long long Ya = o0 / EF * p.Hs + o0 % EF / p.F * p.st, Yb = o1 / EF * p.Hs + o1 % EF / p.F * p.st;
+            if (Yb - Ya + R + wrap > p.Hb) return 1;
+        }
+    }
     size_t pos = 0, real = 0;
     for (int kb = 0; kb < p.kblocks; ++kb)
         for (int ch = 0; ch < p.nchunks; ++ch) {
@@ -497,7 +624,7 @@ int check_plan(const Csr& csr, int C, int R, int S, int elem_bytes, const Plan& 
                             const float wv = csr.val32[(size_t)(lo + t - csr.colidx.data())];
                             uint32_t wb;
                             __builtin_memcpy(&wb, &wv, 4);
-                            const long long elem = (long long)(c - c0) * p.CS + (long long)r * p.pitch + sx;
+                            const long long elem = (long long)(c - c0) * p.CS + ((long long)r * p.pitch + sx) * ge;
                             if (e.wbits != wb || (long long)e.off != elem * ub) return 5;   // weight and tap
                             if (elem + lane_reach >= (long long)(c1 - c0) * p.CS) return 6;  // inside the chunk's tile
                             last_off = e.off;

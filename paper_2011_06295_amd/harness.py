@@ -110,15 +110,15 @@ class Network:
 
         for li, run in enumerate(self.runs):
             d = run.layer.get_launch(*geom(run))
-            tuned = [d["V"], d["WP"], d["WK"], d["KW"], d["Cc"], 0, d["LP"], d["kblocks"], d["store"]]
+            tuned = [d["V"], d["WP"], d["WK"], d["KW"], d["Cc"], 0, d["LP"], d["kblocks"], d["store"], d["lanes"]]
             run.layer.set_launch([])                 # back to the estimate (this discards the measured choice)
             cands = [tuned]
             for c in run.layer.rank_launches(*geom(run), max_candidates=top):
-                if c[:8] not in [k[:8] for k in cands]:
+                if c[:8] + c[9:] not in [k[:8] + k[9:] for k in cands]:
                     cands.append(c)
             timed = sorted((time_layer(li, c), c) for c in cands)
             for t, c in list(timed[:2]):
-                other = c[:8] + [3 - c[8]]
+                other = c[:8] + [3 - c[8]] + c[9:]
                 timed.append((time_layer(li, other), other))
             run.layer.set_launch(min(timed)[1])
         return [run.layer.get_launch(*geom(run)) for run in self.runs]

@@ -95,7 +95,15 @@ def test_argument_validation_returns_status_codes():
     assert lib.sparse_conv_set_launch(h, bad, 6) == B.SC_EINVAL                                  # V must be a power of two
     lp3 = (C.c_int * 7)(0, 0, 0, 0, 0, 0, 3)
     assert lib.sparse_conv_set_launch(h, lp3, 7) == B.SC_EINVAL                                  # positions per lane: 1 or 2
-    assert lib.sparse_conv_set_launch(h, lp3, 10) == B.SC_EINVAL                                 # at most 9 parameters
+    assert lib.sparse_conv_set_launch(h, lp3, 11) == B.SC_EINVAL                                 # at most 10 parameters
+    ln = (C.c_int * 10)(0, 0, 0, 0, 0, 0, 0, 0, 0, 4)
+    assert lib.sparse_conv_set_launch(h, ln, 10) == B.SC_EINVAL                                  # lanes: 0, 1 or 1 + a power of two
+    ln[9] = 33
+    assert lib.sparse_conv_set_launch(h, ln, 10) == B.SC_EINVAL
+    ln[9], ln[6] = 5, 2
+    assert lib.sparse_conv_set_launch(h, ln, 10) == B.SC_EINVAL                                  # output lanes hold one output each
+    ln[6] = 1
+    assert lib.sparse_conv_set_launch(h, ln, 10) == B.SC_OK
     st3 = (C.c_int * 9)(0, 0, 0, 0, 0, 0, 0, 0, 3)
     assert lib.sparse_conv_set_launch(h, st3, 9) == B.SC_EINVAL                                  # kind of output store: 1 or 2
     st3[8] = 2
@@ -227,7 +235,10 @@ def test_plans_hold_every_stored_weight_once_random_shapes_and_launches():
         w, m, _ = rand_layer(rng, 1, Cn, K, R, S, H, W, density=float(rng.choice([0.02, 0.1, 0.3, 0.7])))
         vmax = 8 if dtype == "f16" else 4
         launch = [int(rng.choice([0, 1, 2, 4, vmax])), int(rng.choice([0, 1, 2, 3, 4])), int(rng.choice([0, 1, 2, 3, 5, 8])),
-                  int(rng.choice([0, 1, 2, 4, 8, 16])), int(rng.choice([0, 0, 1, 2, 3, 7, 16])), 0, int(rng.choice([0, 1, 2]))]
+                  int(rng.choice([0, 1, 2, 4, 8, 16])), int(rng.choice([0, 0, 1, 2, 3, 7, 16])), 0, int(rng.choice([0, 1, 2])),
+                  0, 0, int(rng.choice([0, 0, 1, 2, 3, 5, 9, 17]))]     # last: what a lane stands for (1 + G: outputs)
+        if launch[9] > 1:
+            launch[6] = int(rng.choice([0, 1]))
         if rng.integers(0, 3) == 0:
             launch = [0]
         layer = B.SparseConv(w, m, dtype=dtype, unify=bool(rng.integers(0, 2)))
