@@ -223,7 +223,7 @@ def main():
             "bound": bound[0], "roof_frac": round(bound[1] / t, 4),
             "hbm_GBs": round(roofs["hbm_bytes"] / t / 1e9, 1), "lds_GBs": round(roofs["lds_bytes"] / t / 1e9, 1),
             "launch": {k: v for k, v in r.layer.get_launch(N, r.spec.H, r.spec.W, r.spec.stride, r.spec.pad).items()
-                       if k in ("V", "WP", "WK", "KW", "Cc", "LP", "kblocks", "store", "lanes", "grid", "lds_bytes", "threads")},
+                       if k in ("V", "WP", "WK", "KW", "Cc", "LP", "kblocks", "store", "lanes", "csplit", "grid", "lds_bytes", "threads")},
         })
 
     if args.copy_probe_mib > 0:

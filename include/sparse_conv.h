@@ -95,6 +95,9 @@ int sparse_conv_output_shape(sparse_conv_t h, int H, int W, int stride, int pad,
  * and uploads a per-geometry plan (one synchronous allocation + copy);
  * further calls with the same geometry allocate nothing and enqueue exactly one
  * kernel, so they may be recorded into a HIP graph on a capturing stream.
+ * A plan whose channels are dealt over several workgroups (launch parameter [10]) owns a
+ * scratch buffer of partial sums and arrival counters: two forwards of one handle and
+ * geometry must then not run at the same time (different streams without ordering).
  * Limits: input and output below 2^31 elements each (SC_EUNSUPPORTED beyond).
  * Non-finite input values: an output that the definition makes +-Inf may come
  * out as NaN (the stored rows are padded to multiples of four taps by repeating
@@ -171,7 +174,7 @@ int sparse_conv_get_codebook(sparse_conv_t h, const unsigned char** codes, const
 /*
  * sparse_conv_set_launch - override the per-layer launch configuration, this
  * library's counterpart of the per-layer thread-block count the paper tunes
- * (section 8, subBatchSize; section 9).  params[0..nparams), nparams <= 10, are, in order:
+ * (section 8, subBatchSize; section 9).  params[0..nparams), nparams <= 11, are, in order:
  *   [0] V   images interleaved per LDS element (1, 2, 4 or 8; 0 = automatic)
  *   [1] WP  wavefronts across output positions (64 * LP positions each) per workgroup
  *   [2] WK  wavefronts across output channels per workgroup (WP*WK <= 16)
@@ -191,6 +194,12 @@ int sparse_conv_get_codebook(sparse_conv_t h, const unsigned char** codes, const
  *           output element, with G groups of V images interleaved element by element in the
  *           tile (no lane is spent on padding; needs LP = 1).  Which is faster depends on the
  *           map size; sparse_conv_autotune measures both kinds.
+ *   [10] workgroups the input channels of one (tile, channel block) are dealt over: 1, 2, 4 or 8.
+ *           With more than one, each works through its share of the channel chunks and leaves
+ *           its partial sums in a scratch buffer of the plan; the one that finishes last adds them
+ *           up, in the order of the shares (the result does not depend on which one that is),
+ *           and stores.  It pays where a layer has too few tiles and channel blocks to fill the
+ *           chip with workgroups that have many rows each (the 2x2 and 4x4 maps of a deep stack).
  * Missing trailing entries and zeros mean "automatic".  nparams = 0 restores
  * the automatic choice.  Cached plans are discarded.  SC_EINVAL for values the
  * kernels cannot run; a configuration that cannot fit is reported by forward.
@@ -222,7 +231,7 @@ int sparse_conv_autotune(sparse_conv_t h, const void* input, void* output,
  * that measure in their own setting (inside a pass through a network, say): up to
  * max_candidates launch configurations for the geometry, cheapest cost estimate first,
  * within whatever sparse_conv_set_launch has pinned (the list goes round the kinds of
- * lanes: the best of each kind, then the second best of each, ...).  params receives 10 ints per
+ * lanes: the best of each kind, then the second best of each, ...).  params receives 11 ints per
  * candidate, in the order sparse_conv_set_launch takes them (each can be passed back to
  * it as it is); *count the number written.  Needs no GPU.
  */
@@ -256,7 +265,7 @@ int sparse_conv_check_plan(sparse_conv_t h, int N, int H, int W, int stride, int
  * per workgroup, [8] threads per workgroup, [9] stored plan entries
  * (including batch padding), [10] LP, [11] channel blocks, [12] kind of output store
  * (1 or 2), [13] what a lane stands for (1, or 1 + G, as sparse_conv_set_launch takes it),
- * [14], [15] reserved (0).  [0..5] are in the order of sparse_conv_set_launch.  Builds the plan's
+ * [14] workgroups the channels are dealt over, [15] reserved (0).  [0..5] are in the order of sparse_conv_set_launch.  Builds the plan's
  * host side if needed; needs no GPU.  params must have room for 16 ints. */
 int sparse_conv_get_launch(sparse_conv_t h, int N, int H, int W, int stride, int pad, int* params);
 

@@ -194,17 +194,17 @@ def sparse_conv_get_launch(handle: int, N: int, H: int, W: int, stride: int, pad
     arr = (C.c_int * 16)()
     _check(_lib.sparse_conv_get_launch(handle, N, H, W, stride, pad, arr), "sparse_conv_get_launch", handle)
     names = ("V", "WP", "WK", "KW", "Cc", "lds_budget", "grid", "lds_bytes", "threads", "entries", "LP", "kblocks", "store",
-             "lanes")
+             "lanes", "csplit")
     return dict(zip(names, list(arr)))
 
 
 def sparse_conv_rank_launches(handle: int, N: int, H: int, W: int, stride: int, pad: int, max_candidates: int = 8):
-    """The best-ranked launch configurations for a geometry, each a list of 10 ints that sparse_conv_set_launch takes."""
-    arr = (C.c_int * (10 * max_candidates))()
+    """The best-ranked launch configurations for a geometry, each a list of 11 ints that sparse_conv_set_launch takes."""
+    arr = (C.c_int * (11 * max_candidates))()
     n = C.c_int(0)
     _check(_lib.sparse_conv_rank_launches(handle, N, H, W, stride, pad, max_candidates, arr, C.byref(n)),
            "sparse_conv_rank_launches", handle)
-    return [list(arr[10 * i:10 * i + 10]) for i in range(n.value)]
+    return [list(arr[11 * i:11 * i + 11]) for i in range(n.value)]
 
 
 def sparse_conv_check_plan(handle: int, N: int, H: int, W: int, stride: int, pad: int) -> int:

@@ -31,6 +31,8 @@ Plan::~Plan()
     if (d_entries) (void)hipFree(d_entries);
     if (d_seg) (void)hipFree(d_seg);
     if (d_krow) (void)hipFree(d_krow);
+    if (d_partial) (void)hipFree(d_partial);
+    if (d_counters) (void)hipFree(d_counters);
 }
 
 namespace {
@@ -156,6 +158,12 @@ void fill_args(const sparse_conv_s* h, const Plan* p, const void* input, void* o
     a.fd_SP = make_fastdiv(p->SP);
     a.pitch = p->pitch;
     a.fd_pitch = make_fastdiv(p->pitch);
+    a.J = p->J;
+    a.logJ = 0;
+    while ((1 << a.logJ) < p->J) ++a.logJ;
+    a.cpp = p->cpp;
+    a.partial = nullptr;
+    a.counters = nullptr;
     a.real = p->G ? 1 : 0;
     a.logG = 0;
     while ((1 << a.logG) < p->G) ++a.logG;
@@ -175,6 +183,13 @@ std::mutex g_static_lock;
 unsigned long long g_static_holds[64] = {};
 
 size_t round256(size_t n) { return (n + 255) / 256 * 256; }
+
+// Scratch of a plan whose channels are dealt over J > 1 workgroups: partial sums and arrival counters.
+size_t partial_bytes(const Plan& p)
+{
+    return p.J > 1 ? (size_t)p.ntiles * p.kblocks * p.J * ((size_t)p.KW * p.LP * p.V) * p.threads * sizeof(float) : 0;
+}
+size_t counter_bytes(const Plan& p) { return p.J > 1 ? (size_t)p.ntiles * p.kblocks * sizeof(unsigned) : 0; }
 
 // Both forward entry points.  use_static: the plan's tables are read from the GPU's static
 // scratch array (copied there by this call unless the previous call left them) instead of from
@@ -203,17 +218,36 @@ int forward_impl(sparse_conv_s* h, const void* input, void* output, int N, int H
                 if ((rc = upload(h, p->image, &p->d_entries)) != SC_OK) return rc;
                 if ((rc = upload(h, p->seg, &p->d_seg)) != SC_OK) return rc;
                 if ((rc = upload(h, p->krow, &p->d_krow)) != SC_OK) return rc;
+                if (p->J > 1) {
+                    hipError_t he = hipSuccess;
+                    if (!p->d_partial) he = hipMalloc(&p->d_partial, partial_bytes(*p));
+                    if (he == hipSuccess && !p->d_counters) {
+                        he = hipMalloc(&p->d_counters, counter_bytes(*p));
+                        if (he == hipSuccess) he = hipMemset(p->d_counters, 0, counter_bytes(*p));
+                        if (he != hipSuccess && p->d_counters) {
+                            (void)hipFree(p->d_counters);
+                            p->d_counters = nullptr;
+                        }
+                    }
+                    if (he != hipSuccess) {
+                        h->last_hip = (int)he;
+                        return he == hipErrorOutOfMemory ? SC_ENOMEM : SC_EHIP;
+                    }
+                }
                 p->uploaded = true;
             }
             a.entries = static_cast<const uint32_t*>(p->d_entries);
             a.seg = static_cast<const int*>(p->d_seg);
             a.krow = static_cast<const int*>(p->d_krow);
+            a.partial = static_cast<float*>(p->d_partial);
+            a.counters = static_cast<unsigned*>(p->d_counters);
         } else {
             build_image(*p);
             const size_t b_entries = p->image.size() * sizeof(Batch), b_seg = p->seg.size() * sizeof(int),
                          b_krow = p->krow.size() * sizeof(int);
             const size_t at_seg = round256(b_entries), at_krow = at_seg + round256(b_seg);
-            if (at_krow + round256(b_krow) > kStaticScratchBytes) return SC_ETOOBIG;
+            const size_t at_counters = at_krow + round256(b_krow), at_partial = at_counters + round256(counter_bytes(*p));
+            if (at_partial + partial_bytes(*p) > kStaticScratchBytes) return SC_ETOOBIG;
             void* base = nullptr;
             int e = static_scratch(&base);
             if (e != 0) {
@@ -229,6 +263,8 @@ int forward_impl(sparse_conv_s* h, const void* input, void* output, int N, int H
                 hipError_t he = hipMemcpyAsync(d, p->image.data(), b_entries, hipMemcpyHostToDevice, s);
                 if (he == hipSuccess) he = hipMemcpyAsync(d + at_seg, p->seg.data(), b_seg, hipMemcpyHostToDevice, s);
                 if (he == hipSuccess) he = hipMemcpyAsync(d + at_krow, p->krow.data(), b_krow, hipMemcpyHostToDevice, s);
+                // the counters start at zero (every launch leaves them there); whatever the array held before goes
+                if (he == hipSuccess && p->J > 1) he = hipMemsetAsync(d + at_counters, 0, counter_bytes(*p), s);
                 if (he != hipSuccess) {
                     h->last_hip = (int)he;
                     return SC_EHIP;
@@ -238,6 +274,8 @@ int forward_impl(sparse_conv_s* h, const void* input, void* output, int N, int H
             a.entries = reinterpret_cast<const uint32_t*>(d);
             a.seg = reinterpret_cast<const int*>(d + at_seg);
             a.krow = reinterpret_cast<const int*>(d + at_krow);
+            a.counters = p->J > 1 ? reinterpret_cast<unsigned*>(d + at_counters) : nullptr;
+            a.partial = p->J > 1 ? reinterpret_cast<float*>(d + at_partial) : nullptr;
         }
         const int e = launch_tile_kernel(h->dtype, p->V, p->KW, p->LP, a, p->grid, p->threads, p->lds_bytes, stream);
         if (e != 0) {
@@ -340,8 +378,8 @@ int sparse_conv_get_csr(sparse_conv_t h, int* K, long long* nnz,
 
 int sparse_conv_set_launch(sparse_conv_t h, const int* params, int nparams)
 {
-    if (!h || nparams < 0 || nparams > 10 || (nparams > 0 && !params)) return SC_EINVAL;
-    int v[10] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+    if (!h || nparams < 0 || nparams > 11 || (nparams > 0 && !params)) return SC_EINVAL;
+    int v[11] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
     for (int i = 0; i < nparams; ++i) {
         if (params[i] < 0) return SC_EINVAL;
         v[i] = params[i];
@@ -356,7 +394,9 @@ int sparse_conv_set_launch(sparse_conv_t h, const int* params, int nparams)
     if (v[9] > 1 && v[6] == 2) return SC_EINVAL;                                   // output lanes: one output per lane
     sc::Launch l;
     l.V = v[0]; l.WP = v[1]; l.WK = v[2]; l.KW = v[3]; l.Cc = v[4]; l.lds_budget = v[5]; l.LP = v[6]; l.kblocks = v[7]; l.store = v[8];
+    if (v[10] > 8 || (v[10] & (v[10] - 1))) return SC_EINVAL;                      // channel parts: 1, 2, 4 or 8
     l.lanes = v[9];
+    l.csplit = v[10];
     h->over = l;
     h->plans.clear();
     h->tuned.clear();
@@ -394,7 +434,7 @@ int sparse_conv_get_launch(sparse_conv_t h, int N, int H, int W, int stride, int
         if (rc != SC_OK) return rc;
         const int v[16] = {p->V, p->WP, p->WK, p->KW, p->Cc, h->over.lds_budget,
                            p->grid, p->lds_bytes, p->threads, (int)p->entries.size(), p->LP, p->kblocks, p->store,
-                           1 + p->G, 0, 0};
+                           1 + p->G, p->J, 0};
         std::memcpy(params, v, sizeof(v));
         return SC_OK;
     } catch (...) {
@@ -545,8 +585,8 @@ int sparse_conv_rank_launches(sparse_conv_t h, int N, int H, int W, int stride, 
         const int n = (int)std::min<size_t>(ranked.size(), (size_t)max_candidates);
         for (int i = 0; i < n; ++i) {
             const sc::Launch& l = ranked[i].second;
-            const int v[10] = {l.V, l.WP, l.WK, l.KW, l.Cc, 0, l.LP, l.kblocks, l.store ? l.store : 1, l.lanes};
-            std::memcpy(params + 10 * i, v, sizeof(v));
+            const int v[11] = {l.V, l.WP, l.WK, l.KW, l.Cc, 0, l.LP, l.kblocks, l.store ? l.store : 1, l.lanes, l.csplit};
+            std::memcpy(params + 11 * i, v, sizeof(v));
         }
         *count = n;
         return SC_OK;

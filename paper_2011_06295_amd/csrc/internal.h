@@ -55,6 +55,8 @@ struct Launch {
     int store = 0;    // output stores: 1 ordinary, 2 non-temporal (the output is not read again by this kernel)
     int lanes = 0;    // what a lane stands for: 1 a lattice position, 1 + G (G = 1, 2, 4, 8, 16) an output element, with
                       // G image groups interleaved element by element (see Plan)
+    int csplit = 0;   // parts the input channels of a (tile, channel block) are dealt over (1, 2, 4, 8), each part a
+                      // workgroup of its own; the last one to finish adds the partial sums up
 };
 
 struct Geometry {
@@ -119,6 +121,8 @@ struct Plan {
     long long npos;  // positions of the whole batch = ngroups * Hs * Wp
     int ntiles;    // ceil(npos / span)
     int kblocks;   // ceil(K / (WK*KW))
+    int J;         // parts the channel chunks of a (tile, channel block) are dealt over (one workgroup each)
+    int cpp;       // chunks per part = ceil(nchunks / J)
     int threads;   // 64 * WP * WK
     int nbuf;      // tile buffers in LDS: 2 when there are several chunks
     int SL;        // staging slots per channel = SG * SP
@@ -139,6 +143,8 @@ struct Plan {
     void* d_entries = nullptr;
     void* d_seg = nullptr;
     void* d_krow = nullptr;
+    void* d_partial = nullptr;    // J > 1: partial sums [ntiles * kblocks * J][KW * LP * V][threads] fp32 and ...
+    void* d_counters = nullptr;   // ... one arrival counter per (tile, channel block), zero between launches
     bool uploaded = false;
     ~Plan();
 };
@@ -185,6 +191,9 @@ struct KernelArgs {
     int st_dg, st_dc, st_dp; // nthreads = st_dg * (Cc * SP) + st_dc * SP + st_dp
     int nbuf;                // tile buffers in LDS: 2 when there are several chunks
     int npass;               // staging passes per chunk: ceil(SG * Cc * SP / (kStage * threads))
+    int J, logJ, cpp;        // channel parts per (tile, channel block), its log2, chunks per part
+    float* partial;          // J > 1: partial sums of every part, [item][accumulator][thread]
+    unsigned* counters;      // J > 1: parts of a (tile, channel block) that have delivered theirs
     int real;                // lanes are output elements (else lattice positions)
     int logG;                // log2 of the image groups interleaved per element (0 unless real)
     int PT;                  // real: outputs per tile

@@ -159,11 +159,17 @@ __global__ __launch_bounds__(1024) void tile_kernel(const KernelArgs a)
     // equal contiguous ranges, one per XCD: the XCDs get the same number of
     // workgroups, and a tile's rows, which its neighbours and its other channel
     // blocks stage again, are fetched into one L2 (two where a range ends).
+    // With J > 1 the channel chunks of a (tile, channel block) are dealt over J workgroups (neighbours in the
+    // numbering, hence on one XCD); each walks its own chunks, and the last to finish adds the partial sums up.
     const int bid = blockIdx.x;
     const int item = (bid & 7) * (int)(gridDim.x >> 3) + (bid >> 3);
-    if (item >= a.ntiles * a.kblocks) return;
-    const int tile_id = item / a.kblocks;
-    const int kb = item - tile_id * a.kblocks;
+    if (item >= a.ntiles * a.kblocks * a.J) return;
+    const int pair = item >> a.logJ;                  // (tile, channel block)
+    const int part = item & (a.J - 1);
+    const int tile_id = pair / a.kblocks;
+    const int kb = pair - tile_id * a.kblocks;
+    const int ch_first = part * a.cpp;                // the host gives every part at least one chunk
+    const int ch_end = ch_first + a.cpp < a.nchunks ? ch_first + a.cpp : a.nchunks;
 
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lane = tid & 63;
@@ -232,7 +238,7 @@ __global__ __launch_bounds__(1024) void tile_kernel(const KernelArgs a)
     // batch count of each of the KW rows; the KW segments are contiguous in the
     // entry table.  The descriptor of the next chunk and the first batch of this
     // chunk are requested a phase ahead, so their latency is hidden.
-    const SC_CONSTANT int* sg = as_constant(a.seg) + ((size_t)kb * a.nchunks * a.WK + wk) * (KW + 1);
+    const SC_CONSTANT int* sg = as_constant(a.seg) + (((size_t)kb * a.nchunks + ch_first) * a.WK + wk) * (KW + 1);
     const size_t sg_step = (size_t)a.WK * (KW + 1);
     int d_start = sg[0];
     int d_end = sg[KW + 1];  // the next descriptor's first entry: segments are laid out in descriptor order
@@ -254,7 +260,7 @@ __global__ __launch_bounds__(1024) void tile_kernel(const KernelArgs a)
 #pragma unroll
         for (int kk = 0; kk < KW; ++kk) nb[kk] = d_nb[kk];
         fetch_batch(cur, e);  // the table ends in kBatch slack entries
-        if (ch + 1 < a.nchunks) {
+        if (ch + 1 < ch_end) {
             sg += sg_step;
             d_start = sg[0];
             d_end = sg[KW + 1];
@@ -499,12 +505,12 @@ __global__ __launch_bounds__(1024) void tile_kernel(const KernelArgs a)
 
     __syncthreads();  // slot table complete
     prepare_units();
-    fetch_begin(0);
+    fetch_begin(ch_first);
 #pragma unroll
     for (int t = 0; t < kStage; ++t) fetch_unit(t);
     // the input loads do not wait for the descriptor (requested at the top); what needs it comes after them
-    unsigned warm = touch();  // chunk 0's entries
-    begin_chunk(0);
+    unsigned warm = touch();  // the first chunk's entries
+    begin_chunk(ch_first);
     // while the first loads are in flight: padding rows/columns and absent images are zeroed
     // once and stay zero for the whole kernel (staging writes real elements only)
     for (int u = tid; u < a.nbuf * a.tile_elems; u += nthreads) tile[u] = VT::zero();
@@ -518,25 +524,71 @@ __global__ __launch_bounds__(1024) void tile_kernel(const KernelArgs a)
     __syncthreads();  // chunk 0 is in LDS
     SC_PHASE(0);
     const int tile_bytes = a.tile_elems * (int)sizeof(vec);
-    for (int ch = 0; ch < a.nchunks; ++ch) {
-        const bool more = ch + 1 < a.nchunks;
+    for (int ch = ch_first; ch < ch_end; ++ch) {
+        const bool more = ch + 1 < ch_end;
         if (more) {
             warm = touch();           // chunk ch+1's entries (its descriptor was requested a chunk ago)
             fetch_begin(ch + 1);
         }
         SC_PHASE(1);
-        compute((ch & (a.nbuf - 1)) * tile_bytes + lposb, more);  // chunk ch+1's loads are issued along the way
+        compute(((ch - ch_first) & (a.nbuf - 1)) * tile_bytes + lposb, more);  // chunk ch+1's loads are issued along the way
         SC_PHASE(2);
         if (more) {
             begin_chunk(ch + 1);
-            deposit((ch + 1) & (a.nbuf - 1));
+            deposit((ch + 1 - ch_first) & (a.nbuf - 1));
             retire(warm);
             for (int p = 1; p < a.npass; ++p) {
                 fetch_more(p);
-                deposit((ch + 1) & (a.nbuf - 1));
+                deposit((ch + 1 - ch_first) & (a.nbuf - 1));
             }
             __syncthreads();  // chunk ch+1 is in LDS; everyone is done with chunk ch's buffer
             SC_PHASE(3);
+        }
+    }
+
+    // ---- channel parts: every part leaves its sums in global memory; the one that finds all others done
+    // (a counter per (tile, channel block), back at zero when the launch ends) adds them up in the order of
+    // the parts, whichever came last, and goes on to the store.  The sums travel as device-scope atomic
+    // stores and loads (written through to, and read from, the level all XCDs share) and the arrival is a
+    // device-scope atomic: no cache of the chip is flushed or invalidated as a whole, which a device-scope
+    // fence would do (measured: it made a 27 us layer take 78).  A part's stores are complete (the wait at
+    // the workgroup-scope fence) before its arrival is counted.
+    if (a.J > 1) {
+        constexpr int kAcc = KW * LP * V;
+        float* mine = a.partial + (size_t)item * kAcc * nthreads + tid;
+#pragma unroll
+        for (int kk = 0; kk < KW; ++kk)
+#pragma unroll
+            for (int p = 0; p < LP; ++p)
+#pragma unroll
+                for (int v = 0; v < V; ++v)
+                    __hip_atomic_store(mine + (size_t)((kk * LP + p) * V + v) * nthreads, acc[kk][p][v], __ATOMIC_RELAXED,
+                                       __HIP_MEMORY_SCOPE_AGENT);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // this wavefront's stores have completed
+        __syncthreads();                                         // ... and every wavefront's; nobody reads the tile any more
+        unsigned* ticket = reinterpret_cast<unsigned*>(smem);
+        if (tid == 0) *ticket = __hip_atomic_fetch_add(a.counters + pair, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __syncthreads();
+        if (*ticket != (unsigned)(a.J - 1)) return;
+        if (tid == 0) __hip_atomic_store(a.counters + pair, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const float* all = a.partial + (size_t)(pair << a.logJ) * kAcc * nthreads + tid;
+#pragma unroll
+        for (int kk = 0; kk < KW; ++kk)
+#pragma unroll
+            for (int p = 0; p < LP; ++p)
+#pragma unroll
+                for (int v = 0; v < V; ++v) acc[kk][p][v] = 0.f;
+        for (int j = 0; j < a.J; ++j) {   // in the order of the parts; all loads of a part are in flight together
+            float got[kAcc];
+#pragma unroll
+            for (int i = 0; i < kAcc; ++i)
+                got[i] = __hip_atomic_load(all + ((size_t)j * kAcc + i) * nthreads, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+            for (int kk = 0; kk < KW; ++kk)
+#pragma unroll
+                for (int p = 0; p < LP; ++p)
+#pragma unroll
+                    for (int v = 0; v < V; ++v) acc[kk][p][v] += got[(kk * LP + p) * V + v];
         }
     }
 

@@ -46,6 +46,7 @@ struct Shape {
 struct Cand {
     int V, WP, WK, KW, Cc, LP, kblocks;
     int Hb, CS, lds, SL, rows_mode, SG, nbuf, pitch;
+    int J;
 };
 
 // Output-lane tiles: the most lattice rows between the first and the last of PT consecutive outputs
@@ -116,7 +117,8 @@ void rows_per_wavefront(int nrows, int WP, int WK, int KW, std::vector<int>& roo
 //    last round still takes a round.
 double estimate(const Shape& s, const Cand& c)
 {
-    const int nchunks = cdiv(s.C, c.Cc);
+    const int J = c.J > 0 ? c.J : 1;
+    const int nchunks = cdiv(cdiv(s.C, c.Cc), J);          // chunks a workgroup walks
     const double seg = s.row_nnz * c.Cc / s.C;
     const double batches = nchunks == 1 ? std::ceil(seg / kBatch) : seg / kBatch + 0.8;
     const int waves = c.WP * c.WK;
@@ -125,7 +127,7 @@ double estimate(const Shape& s, const Cand& c)
     const int conc_max = std::min(kMaxLds / c.lds, 4 * per_simd / waves);
     if (conc_max < 1) return -1.0;
     const int kblocks = c.kblocks;
-    const long long wgs = (long long)cdiv(s.npos, (long long)kWave * c.WP * c.LP) * kblocks;
+    const long long wgs = (long long)cdiv(s.npos, (long long)kWave * c.WP * c.LP) * kblocks * J;
     // rows on the fullest SIMD and wavefront-rows in all of a typical channel block
     std::vector<int> room;
     rows_per_wavefront(cdiv(s.K, kblocks), c.WP, c.WK, c.KW, room);
@@ -136,8 +138,9 @@ double estimate(const Shape& s, const Cand& c)
     const double fma_clk = s.elem_bytes == 2 ? 4.4 : 4.0;
     const double v_step = kBatch * (c.LP * c.V * fma_clk + 4.0);
     const double l_step = kBatch * c.LP * 64.0 * s.ub / 225.0;
-    const double gbytes = (double)s.C * c.CS * s.ub * ((double)s.W / s.Wp) * std::min(1.0, (double)s.H / s.Hs);
-    const double fixed = 16000.0 + 1000.0 * nchunks;
+    const double gbytes = (double)s.C / J * c.CS * s.ub * ((double)s.W / s.Wp) * std::min(1.0, (double)s.H / s.Hs);
+    // (parts: writing the partial sums, and the last part reading all of them back)
+    const double fixed = 16000.0 + 1000.0 * nchunks + (J > 1 ? 2500.0 + 600.0 * J : 0.0);
     const double shape_factor = c.KW == 1 ? 1.2 : c.KW == 8 ? 1.05 : 1.0;   // measured residuals
     double t = 0.0;
     long long remaining = wgs;
@@ -212,6 +215,7 @@ int build_plan(const Csr& csr, int C, int R, int S, int elem_bytes, const Geomet
     if (over.LP && !pow2_in(over.LP, 1, 2)) return SC_EINVAL;
     if (over.store < 0 || over.store > 2) return SC_EINVAL;
     if (over.lanes < 0 || (over.lanes > 1 && !pow2_in(over.lanes - 1, 1, 16))) return SC_EINVAL;
+    if (over.csplit && !pow2_in(over.csplit, 1, 8)) return SC_EINVAL;
 
     // ---- candidates
     static const int budgets[] = {160 * 1024, 80 * 1024, 53 * 1024, 40 * 1024, 32 * 1024};
@@ -358,7 +362,11 @@ int build_plan(const Csr& csr, int C, int R, int S, int elem_bytes, const Geomet
                             const int kblocks = over.kblocks ? over.kblocks : kb_min + extra;
                             if (over.kblocks && extra) break;
                             if (kblocks < kb_min || (extra && kblocks > K)) continue;
-                            Cand c{V, wp, wk, kw, Cc, LP, kblocks, Hb, (int)CS, (int)lds, (int)SL, banded ? 2 : rows_mode ? 1 : 0, rows_mode ? 1 : (int)GC, nbuf, pitch};
+                            for (int J = 1; J <= 8; J *= 2) {
+                            if (over.csplit && J != over.csplit) continue;
+                            const int nch = cdiv(C, Cc);
+                            if (J > 1 && (J > nch || (long long)(J - 1) * cdiv(nch, J) >= nch)) continue;   // every part needs a chunk
+                            Cand c{V, wp, wk, kw, Cc, LP, kblocks, Hb, (int)CS, (int)lds, (int)SL, banded ? 2 : rows_mode ? 1 : 0, rows_mode ? 1 : (int)GC, nbuf, pitch, J};
                             double t = estimate(s, c);
                             if (t < 0) {
                                 if (!(over.WP || over.WK || over.KW || over.Cc || over.lds_budget || over.LP || over.kblocks)) continue;
@@ -369,12 +377,14 @@ int build_plan(const Csr& csr, int C, int R, int S, int elem_bytes, const Geomet
                                 l.V = V; l.WP = wp; l.WK = wk; l.KW = kw; l.Cc = Cc; l.LP = LP; l.kblocks = kblocks;
                                 l.store = over.store;
                                 l.lanes = 1 + G;
+                                l.csplit = J;
                                 ranked->emplace_back(t, l);
                             }
                             if (best_t < 0 || t < best_t) {
                                 best_t = t;
                                 best = c;
                                 bs = s;
+                            }
                             }
                         }
                     }
@@ -394,7 +404,8 @@ int build_plan(const Csr& csr, int C, int R, int S, int elem_bytes, const Geomet
             for (const auto& u : uniq)
                 seen = seen || (u.second.V == e.second.V && u.second.WP == e.second.WP && u.second.WK == e.second.WK &&
                                 u.second.KW == e.second.KW && u.second.Cc == e.second.Cc && u.second.LP == e.second.LP &&
-                                u.second.kblocks == e.second.kblocks && u.second.lanes == e.second.lanes);
+                                u.second.kblocks == e.second.kblocks && u.second.lanes == e.second.lanes &&
+                                u.second.csplit == e.second.csplit);
             if (!seen) uniq.push_back(e);
             if (uniq.size() >= 256) break;
         }
@@ -405,9 +416,9 @@ int build_plan(const Csr& csr, int C, int R, int S, int elem_bytes, const Geomet
             std::vector<std::pair<double, Launch>> mixed;
             std::vector<char> used(uniq.size(), 0);
             while (mixed.size() < uniq.size() && mixed.size() < 64) {
-                bool took[18] = {};
+                bool took[36] = {};
                 for (size_t i = 0; i < uniq.size() && mixed.size() < 64; ++i) {
-                    const int kind = uniq[i].second.lanes;
+                    const int kind = uniq[i].second.lanes + (uniq[i].second.csplit > 1 ? 18 : 0);
                     if (used[i] || took[kind]) continue;
                     took[kind] = true;
                     used[i] = 1;
@@ -436,6 +447,8 @@ int build_plan(const Csr& csr, int C, int R, int S, int elem_bytes, const Geomet
     const long long ntiles = (s.npos + p.span - 1) / p.span;
     const int KB = p.WK * p.KW;
     p.kblocks = best.kblocks;
+    p.J = best.J;
+    p.cpp = cdiv(cdiv(C, p.Cc), p.J);
     p.threads = kWave * p.WP * p.WK;
     p.lds_bytes = best.lds;
     p.SL = best.SL;
@@ -445,7 +458,7 @@ int build_plan(const Csr& csr, int C, int R, int S, int elem_bytes, const Geomet
     p.pitch = best.pitch;
     p.nbuf = best.nbuf;
     p.tbl_off = (p.nbuf * (p.Cc * p.CS + 1) * s.ub + 15) / 16 * 16;
-    const long long grid = (ntiles * p.kblocks + 7) / 8 * 8;   // a multiple of the XCD count
+    const long long grid = (ntiles * p.kblocks * p.J + 7) / 8 * 8;   // a multiple of the XCD count
     if (ntiles > INT_MAX / 2 || grid > INT_MAX - 8) return SC_EUNSUPPORTED;
     p.ntiles = (int)ntiles;
     p.grid = (int)grid;
@@ -565,7 +578,8 @@ int check_plan(const Csr& csr, int C, int R, int S, int elem_bytes, const Plan& 
     if (p.nchunks != cdiv(C, p.Cc) || (p.nbuf != 1 && p.nbuf != 2) || (p.nchunks > 1 && p.nbuf != 2)) return 1;
     if ((long long)p.tbl_off + (long long)p.SL * 8 > p.lds_bytes) return 1;
     if ((long long)p.nbuf * ((long long)p.Cc * p.CS + 1) * ub > p.tbl_off) return 1;
-    if ((long long)p.grid < (long long)p.ntiles * p.kblocks || p.grid % 8 != 0) return 1;
+    if ((long long)p.grid < (long long)p.ntiles * p.kblocks * p.J || p.grid % 8 != 0) return 1;
+    if (p.J < 1 || p.J > 8 || (p.J & (p.J - 1)) || p.cpp != cdiv(p.nchunks, p.J) || (long long)(p.J - 1) * p.cpp >= p.nchunks) return 1;
     if ((long long)p.ntiles * p.span < p.npos || (long long)(p.ntiles - 1) * p.span >= p.npos) return 1;
     // 2: every output channel owns exactly one accumulator slot
     if (p.krow.size() != (size_t)p.kblocks * KB) return 2;

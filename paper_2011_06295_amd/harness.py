@@ -110,7 +110,7 @@ class Network:
 
         for li, run in enumerate(self.runs):
             d = run.layer.get_launch(*geom(run))
-            tuned = [d["V"], d["WP"], d["WK"], d["KW"], d["Cc"], 0, d["LP"], d["kblocks"], d["store"], d["lanes"]]
+            tuned = [d["V"], d["WP"], d["WK"], d["KW"], d["Cc"], 0, d["LP"], d["kblocks"], d["store"], d["lanes"], d["csplit"]]
             run.layer.set_launch([])                 # back to the estimate (this discards the measured choice)
             cands = [tuned]
             for c in run.layer.rank_launches(*geom(run), max_candidates=top):

@@ -95,7 +95,13 @@ def test_argument_validation_returns_status_codes():
     assert lib.sparse_conv_set_launch(h, bad, 6) == B.SC_EINVAL                                  # V must be a power of two
     lp3 = (C.c_int * 7)(0, 0, 0, 0, 0, 0, 3)
     assert lib.sparse_conv_set_launch(h, lp3, 7) == B.SC_EINVAL                                  # positions per lane: 1 or 2
-    assert lib.sparse_conv_set_launch(h, lp3, 11) == B.SC_EINVAL                                 # at most 10 parameters
+    assert lib.sparse_conv_set_launch(h, lp3, 12) == B.SC_EINVAL                                 # at most 11 parameters
+    cs = (C.c_int * 11)(0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 3)
+    assert lib.sparse_conv_set_launch(h, cs, 11) == B.SC_EINVAL                                  # channel parts: 1, 2, 4 or 8
+    cs[10] = 16
+    assert lib.sparse_conv_set_launch(h, cs, 11) == B.SC_EINVAL
+    cs[10] = 4
+    assert lib.sparse_conv_set_launch(h, cs, 11) == B.SC_OK
     ln = (C.c_int * 10)(0, 0, 0, 0, 0, 0, 0, 0, 0, 4)
     assert lib.sparse_conv_set_launch(h, ln, 10) == B.SC_EINVAL                                  # lanes: 0, 1 or 1 + a power of two
     ln[9] = 33
@@ -236,7 +242,8 @@ def test_plans_hold_every_stored_weight_once_random_shapes_and_launches():
         vmax = 8 if dtype == "f16" else 4
         launch = [int(rng.choice([0, 1, 2, 4, vmax])), int(rng.choice([0, 1, 2, 3, 4])), int(rng.choice([0, 1, 2, 3, 5, 8])),
                   int(rng.choice([0, 1, 2, 4, 8, 16])), int(rng.choice([0, 0, 1, 2, 3, 7, 16])), 0, int(rng.choice([0, 1, 2])),
-                  0, 0, int(rng.choice([0, 0, 1, 2, 3, 5, 9, 17]))]     # last: what a lane stands for (1 + G: outputs)
+                  0, 0, int(rng.choice([0, 0, 1, 2, 3, 5, 9, 17])),     # what a lane stands for (1 + G: outputs)
+                  int(rng.choice([0, 0, 1, 2, 4, 8]))]                  # workgroups the channels are dealt over
         if launch[9] > 1:
             launch[6] = int(rng.choice([0, 1]))
         if rng.integers(0, 3) == 0:

@@ -249,6 +249,39 @@ def test_lanes_as_outputs(G, dtype):
             check(w, m, x, st, p, dtype, launch=launch, what=f"outputs-G{G}-{dtype}-case{ci}-{launch}")
 
 
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+@pytest.mark.parametrize("J", [2, 4, 8])
+def test_channels_dealt_over_several_workgroups(J, dtype):
+    """The input channels of a (tile, channel block) dealt over J workgroups whose partial sums the last one
+    to finish adds up: against the oracle, every element; repeated launches give the same bits (the sums are
+    added in the order of the parts, and the arrival counters are back at zero after every launch)."""
+    torch = _torch()
+    from paper_2011_06295_amd import binding as B
+    rng = np.random.default_rng(900 + J)
+    cases = [(37, 96, 40, 3, 3, 2, 2, 1, 1, [4, 0, 0, 0, 48 // J, 0, 0, 0, 0, 1, J]),     # lattice lanes, two chunks a part
+             (70, 64, 24, 3, 3, 4, 4, 1, 1, [4, 1, 3, 2, 32 // J, 0, 1, 0, 0, 9, J]),     # output lanes
+             (9, 40, 50, 3, 3, 9, 11, 2, 1, [0, 2, 2, 4, 40 // J, 0, 2, 0, 2, 1, J]),     # two positions per lane, one chunk a part
+             (130, 32, 17, 1, 1, 3, 3, 1, 0, [0, 0, 0, 0, 4, 0, 0, 0, 0, 0, J])]    # automatic kind of lanes
+    for ci, (N, C, K, R, S, H, W, st, p, launch) in enumerate(cases):
+        w, m, x = rand_layer(rng, N, C, K, R, S, H, W, density=0.3)
+        layer = B.SparseConv(w, m, dtype=dtype)
+        layer.set_launch(launch)
+        info = layer.get_launch(N, H, W, st, p)
+        print(f"channel parts {J} {dtype} case {ci}: {info}", flush=True)
+        assert info["csplit"] == J
+        xt = torch.from_numpy(x).cuda()
+        xt = (xt.half() if dtype == "f16" else xt).contiguous()
+        ref = oracle_ref(w, m, x, st, p, dtype)
+        first = None
+        for rep in range(3):
+            y = layer.forward(xt, st, p)
+            torch.cuda.synchronize()
+            assert_close(y.float().cpu().numpy(), ref, TOL[dtype], f"parts{J}-{dtype}-case{ci}-rep{rep}")
+            first = y.clone() if first is None else first
+            assert torch.equal(y, first), f"parts{J}-{dtype}-case{ci}: launch {rep} differs from the first"
+        layer.close()
+
+
 @pytest.mark.parametrize("seed", [7, 11, 23])
 def test_random_shapes_with_random_launch_overrides(seed):
     """Random geometry (filters up to 5x5, stride 1..3, pad 0..3, maps up to 40 x 200) crossed with random
@@ -269,7 +302,7 @@ def test_random_shapes_with_random_launch_overrides(seed):
         vmax = 8 if dtype == "f16" else 4
         launch = [int(rng.choice([0, 1, 2, 4, vmax])), int(rng.choice([0, 1, 2, 3, 4])), int(rng.choice([0, 1, 2, 3, 5, 8])),
                   int(rng.choice([0, 1, 2, 4, 8, 16])), int(rng.choice([0, 0, 1, 2, 3, 7, 16])), 0, int(rng.choice([0, 1, 2])),
-                  0, int(rng.choice([0, 1, 2])), int(rng.choice([0, 1, 2, 3, 5, 9, 17]))]
+                  0, int(rng.choice([0, 1, 2])), int(rng.choice([0, 1, 2, 3, 5, 9, 17])), int(rng.choice([0, 0, 1, 2, 4, 8]))]
         if launch[9] > 1:                 # lanes stand for outputs (G image groups interleaved): one output per lane
             launch[6] = int(rng.choice([0, 1]))
         if rng.integers(0, 3) == 0:

@@ -35,8 +35,11 @@ def test_static_entry_point_matches_forward_twice_in_a_row(dtype):
     w2, m2, xc = rand_layer(rng, 9, 7, 5, 1, 1, 6, 6, density=0.5)
     other = B.SparseConv(w2, m2, dtype=dtype)
     xb = xa[:5, :, :7, :6].copy()                      # smaller batch and map
+    split = B.SparseConv(w, m, dtype=dtype)           # its channels dealt over 4 workgroups: partial sums and counters
+    split.set_launch([0, 0, 0, 0, 3, 0, 0, 0, 0, 0, 4])   # live in the scratch as well
     calls = [(layer, w, m, xa, 1, 1), (layer, w, m, xb, 2, 1), (layer, w, m, xa, 1, 1), (other, w2, m2, xc, 1, 0),
-             (layer, w, m, xb, 2, 1)]
+             (layer, w, m, xb, 2, 1), (split, w, m, xa, 1, 1), (split, w, m, xa, 1, 1), (split, w, m, xb, 2, 1),
+             (layer, w, m, xa, 1, 1), (split, w, m, xb, 2, 1)]
     for step, (lay, ww, mm, x, stride, pad) in enumerate(calls):
         xt = torch.from_numpy(x).cuda().to(tdt).contiguous()
         E, F = lay.output_shape(x.shape[2], x.shape[3], stride, pad)
@@ -55,6 +58,7 @@ def test_static_entry_point_matches_forward_twice_in_a_row(dtype):
         assert_close(got.float().cpu().numpy(), ref, TOL[dtype], f"static call {step}")
     layer.close()
     other.close()
+    split.close()
 
 
 def test_static_entry_point_rejects_tables_beyond_the_scratch():
