@@ -20,10 +20,11 @@ import numpy as np
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
-# MI355X published peaks used for the roofline
-HBM_PEAK = 8.0e12                      # B/s
-LDS_PEAK = 256 * 256 * 2.4e9           # 256 CUs x 256 B/clk (wide LDS reads) x 2.4 GHz = 157.3 TB/s
-VALU_PEAK_FMA = 256 * 128 * 2.4e9      # fp32 vector: 157.3 TFLOP/s = 78.6e12 FMA/s
+from paper_2011_06295_amd.roofs import (HBM_PEAK, LDS_PEAK, VALU_PEAK_FMA, MEASURED_LDS_B_PER_CLK_PER_CU,  # noqa: E402
+                                        MEASURED_COPY_BYTES_PER_S, CUS, CLOCK_HZ, PROFILE as ROOF_PROFILE)
+
+# what the default run reports beside the headline (configs 2, 4, 5 and 1 of the benchmark list)
+CONFIG_LINES = ("vgg16_f16", "sweep90", "sweep95", "sweep99", "sweep90r", "lenet5", "config1")
 
 
 def make_workload(name: str):
@@ -61,11 +62,7 @@ def layer_roofs(run, N, b):
     }
 
 
-# mean HBM-side bytes per launch of sc::tile_kernel (see profiles/)
-MEASURED_TRAFFIC = {"vgg16_f32": 27.7e6, "vgg16_f16": 31.1e6}
-
-
-def oracle_leg(net, work, budget_s=12.0, npts=2000):
+def oracle_leg(net, work, budget_s=12.0, npts=2000, time_it=True):
     """The CPU oracle leg, after the timed region: (1) sampled outputs of every layer, as the timed launches
     left them in the first buffer set, against the oracle's exact-order double sums of the same operands;
     (2) the oracle itself (float accumulation, one thread) timed on the first n images of every layer."""
@@ -92,7 +89,7 @@ def oracle_leg(net, work, budget_s=12.0, npts=2000):
         checked += npts
     parity = {"checked": checked, "max_rel": worst, "tolerance": tol, "ok": bool(worst <= tol),
               "rule": "max |gpu - oracle| / max |oracle| per layer, sampled outputs of the timed launches"}
-    return parity, cpu_baseline(oracle, net, work, budget_s)
+    return parity, (cpu_baseline(oracle, net, work, budget_s) if time_it else None)
 
 
 def cpu_baseline(oracle, net, work, budget_s=12.0):
@@ -132,7 +129,14 @@ def main():
                     help="vgg16_f32 (default: VGG-16 for 32x32 images, batch 128), vgg16_f16 (batch 256), lenet5, config1, "
                          "sweepNN / sweepNNr (256->256 14x14 layer at NN %% sparsity, unified / ragged rows), "
                          "resnet1x1, densenet1x1, cnn1d, vgg16_224 (each also with _f16)")
-    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg (sampled comparison and baseline timing)")
+    ap.add_argument("--configs", type=int, default=1,
+                    help="1: the default workload's line also carries `configs`, the other benchmark configurations "
+                         "(vgg16_f16, the 14x14 layer at 90/95/99 %% and with ragged rows, lenet5, config1), each tuned and "
+                         "timed by the same protocol; 0: the one workload only")
+    ap.add_argument("--probe", action="store_true",
+                    help="measure the roofs instead of a workload: LDS read rate of the gather's access pattern and the "
+                         "rate of a plain copy, with the library's probe kernels; prints one JSON line")
     ap.add_argument("--launch", default="", help="comma separated launch override applied to every layer")
     ap.add_argument("--autotune", type=int, default=8,
                     help="before the warm-up, let every layer measure this many of its best-ranked launch "
@@ -162,9 +166,74 @@ def main():
     import torch
     if not torch.cuda.is_available():
         raise SystemExit("bench.py needs a GPU (there is no CPU fallback of the product path)")
+    if args.probe:
+        print(json.dumps(probe_roofs()))
+        return
+    out = run_workload(args.workload, args, args.steps, args.warmup, brief=False)
+    if args.configs and args.workload == "vgg16_f32" and not args.launch and not args.unify:
+        # the other benchmark configurations, each tuned and timed by the same protocol (fewer steps, no
+        # per-layer table, no CPU timing; the sampled comparison with the oracle stays)
+        out["configs"] = []
+        for name in CONFIG_LINES:
+            r = run_workload(name, args, min(args.steps, 20), min(args.warmup, 5), brief=True)
+            line = {"workload": name, "batch": r["config"]["batch"], "dtype": r["dtype"], "ms_per_step": r["ms_per_step"],
+                    "value": r["value"], "unit": r["unit"], "bound": r["roofline"]["bound"],
+                    "roofline_frac": r["roofline"]["frac"], "lds_frac": r["roofline"]["lds_frac"],
+                    "launches_per_step": r["roofline"]["launches_per_step"]}
+            if "parity" in r:
+                line["parity"] = {k: r["parity"][k] for k in ("checked", "max_rel", "ok")}
+            out["configs"].append(line)
+    print(json.dumps(out))
+
+
+def probe_roofs():
+    """Measured roofs: the LDS read rate of the gather's access pattern and the rate of a plain copy."""
+    import torch
+    from paper_2011_06295_amd import binding as B
+    stream = torch.cuda.current_stream().cuda_stream
+    out = {"clock_hz_assumed": CLOCK_HZ, "cus": CUS}
+    wgs, iters = CUS * 4, 4000
+    sink = torch.empty(wgs * 1024, dtype=torch.float32, device="cuda")
+    B.sparse_conv_probe_lds_read(sink.data_ptr(), wgs, 50, stream)
+    torch.cuda.synchronize()
+    best = None
+    for _ in range(3):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        nbytes = B.sparse_conv_probe_lds_read(sink.data_ptr(), wgs, iters, stream)
+        e1.record()
+        torch.cuda.synchronize()
+        t = e0.elapsed_time(e1) * 1e-3
+        best = t if best is None else min(best, t)
+    out["lds_read_TBs"] = nbytes / best / 1e12
+    out["lds_B_per_clk_per_CU"] = nbytes / best / CUS / CLOCK_HZ
+    out["lds_frac_of_published"] = nbytes / best / LDS_PEAK
+    n = 1 << 30
+    src = torch.empty(n, dtype=torch.uint8, device="cuda").random_(0, 255)
+    dst = torch.empty_like(src)
+    B.sparse_conv_probe_copy(dst.data_ptr(), src.data_ptr(), n, stream)
+    torch.cuda.synchronize()
+    best = None
+    for _ in range(5):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        B.sparse_conv_probe_copy(dst.data_ptr(), src.data_ptr(), n, stream)
+        e1.record()
+        torch.cuda.synchronize()
+        t = e0.elapsed_time(e1) * 1e-3
+        best = t if best is None else min(best, t)
+    assert torch.equal(dst, src)
+    out["copy_GiB"] = n >> 30
+    out["copy_read_plus_write_GBs"] = 2 * n / best / 1e9
+    out["copy_frac_of_published_hbm"] = 2 * n / best / HBM_PEAK
+    return out
+
+
+def run_workload(name, args, steps, warmup, brief):
+    import torch
     from paper_2011_06295_amd import harness, workloads as wl
 
-    work, layer_ids = make_workload(args.workload)
+    work, layer_ids = make_workload(name)
     net = harness.Network(work, unify=args.unify, layer_ids=layer_ids)
     if args.launch:
         for r in net.runs:
@@ -185,25 +254,25 @@ def main():
         net.refine_in_context(top=args.refine_top)
 
     def timed(rotate):
-        for i in range(args.warmup):
+        for i in range(warmup):
             net.step(i if rotate else 0)
         torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         t0 = time.perf_counter()
         e0.record()
-        for i in range(args.steps):
+        for i in range(steps):
             net.step(i if rotate else 0)
         e1.record()
         torch.cuda.synchronize()
         return time.perf_counter() - t0, e0.elapsed_time(e1)
 
-    hot_wall, _ = timed(False)
+    hot_wall = timed(False)[0] if not brief else 0.0
     wall, gpu_ms = timed(True)
-    ms_per_step = wall * 1e3 / args.steps
+    ms_per_step = wall * 1e3 / steps
 
     # per-layer durations, in the order and cache state of a step: events between the launches of
     # further (untimed) steps on the launch stream
-    reps = max(10, min(args.steps, 50))
+    reps = 0 if brief else max(10, min(steps, 50))
     marks = [[torch.cuda.Event(enable_timing=True) for _ in range(len(net.runs) + 1)] for _ in range(reps)]
     for j, ev in enumerate(marks):
         ev[0].record()
@@ -214,6 +283,8 @@ def main():
     torch.cuda.synchronize()
     layers = []
     for i, r in enumerate(net.runs):
+        if brief:
+            break
         t = sum(ev[i].elapsed_time(ev[i + 1]) for ev in marks) * 1e-3 / reps
         roofs = layer_roofs(r, N, b)
         bound = max(("hbm", roofs["t_hbm"]), ("lds", roofs["t_lds"]), ("alu", roofs["t_valu"]), key=lambda kv: kv[1])
@@ -237,10 +308,10 @@ def main():
     total_macs = net.total_macs()
     roofs = [layer_roofs(r, N, b) for r in net.runs]
     nl = len(net.runs)
-    avg_launch_s = gpu_ms * 1e-3 / (args.steps * nl)
+    avg_launch_s = gpu_ms * 1e-3 / (steps * nl)
     sums = {k: sum(rf[k] for rf in roofs) for k in ("t_hbm", "t_lds", "t_valu", "lds_bytes", "hbm_bytes")}
-    # the binding roof is the largest of the three times (fp32: LDS and VALU tie, reported as LDS;
-    # fp16: half the LDS bytes per MAC, so the non-packed fp32 multiply-add rate binds)
+    # the binding roof is the largest of the three times (fp32: the LDS read rate and the non-packed multiply-add
+    # rate tie, reported as LDS; fp16: half the LDS bytes per multiply-add, so the multiply-add rate binds)
     if sums["t_valu"] > sums["t_lds"] and sums["t_valu"] >= sums["t_hbm"]:
         roofline = {"bound": "alu", "achieved": 2.0 * total_macs / nl / avg_launch_s / 1e12,
                     "peak": 2.0 * VALU_PEAK_FMA / 1e12, "unit": "TFLOP/s"}
@@ -251,14 +322,15 @@ def main():
         roofline = {"bound": "hbm", "achieved": sums["hbm_bytes"] / nl / avg_launch_s / 1e9, "peak": HBM_PEAK / 1e9,
                     "unit": "GB/s"}
     roofline["frac"] = roofline["achieved"] / roofline["peak"]
-    if roofline["bound"] == "lds":
-        # beside the nominal figure: the ds_read_b128 rate a bare read loop reaches on this chip (225 B/clk/CU),
-        # and the rate of the bare inner loop's own mix of reads and multiply-adds (0.56 of nominal)
-        roofline["frac_of_measured_read_rate"] = roofline["achieved"] / (256 * 225 * 2.4)
-        roofline["frac_of_inner_loop_ceiling"] = roofline["frac"] / 0.56
-    # HBM-side bytes per launch, measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE and scaled by a copy
-    # of known size (profiles/tile_kernel_*_hbm_traffic.md); null for workloads that were not profiled
-    roofline["traffic"] = MEASURED_TRAFFIC.get(args.workload)
+    # the LDS fraction whatever binds, and the same against the read rate measured on this machine (bench.py --probe)
+    roofline["lds_frac"] = sums["lds_bytes"] / nl / avg_launch_s / LDS_PEAK
+    roofline["lds_frac_of_measured_read_rate"] = (sums["lds_bytes"] / nl / avg_launch_s /
+                                                  (MEASURED_LDS_B_PER_CLK_PER_CU * CUS * CLOCK_HZ))
+    roofline["measured_roofs"] = {"lds_B_per_clk_per_CU": MEASURED_LDS_B_PER_CLK_PER_CU,
+                                  "copy_bytes_per_s": MEASURED_COPY_BYTES_PER_S, "source": ROOF_PROFILE}
+    # HBM-side bytes per launch come from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (profiles/); a bench run
+    # does not measure them
+    roofline["traffic"] = None
     roofline["kernel"] = "sc::tile_kernel"
     roofline["avg_launch_us"] = avg_launch_s * 1e6
     roofline["launches_per_step"] = nl
@@ -269,9 +341,9 @@ def main():
         "metric": "effective GFLOP/s (2*nnz*E*F*N over the sparse conv layers of the workload)",
         "value": 2.0 * total_macs / (ms_per_step * 1e-3) / 1e9,
         "unit": "GFLOP/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms_per_step, "gpu_ms_per_step": gpu_ms / args.steps,
-        "cache_hot_ms_per_step": hot_wall * 1e3 / args.steps, "buffer_sets": nsets,
+        "n_gpus": 1, "steps": steps, "warmup": warmup,
+        "ms_per_step": ms_per_step, "gpu_ms_per_step": gpu_ms / steps,
+        "cache_hot_ms_per_step": hot_wall * 1e3 / steps, "buffer_sets": nsets,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": work.dtype, "data": "synthetic",
         "config": {"workload": f"{work.name}, batch {N}, {nl} sparse conv layer(s), conv only, inputs resident in HBM, {nsets} buffer set(s) in rotation",
@@ -299,8 +371,14 @@ def main():
             r.y.fill_(float("nan"))
         net.step(0)
         torch.cuda.synchronize()
-        out["parity"], out["cpu_baseline"] = oracle_leg(net, work)
-    print(json.dumps(out))
+        parity, cpu = oracle_leg(net, work, npts=500 if brief else 2000, time_it=not brief)
+        out["parity"] = parity
+        if cpu is not None:
+            out["cpu_baseline"] = cpu
+    net.close()
+    del net
+    torch.cuda.empty_cache()
+    return out
 
 
 if __name__ == "__main__":

@@ -269,6 +269,21 @@ int sparse_conv_check_plan(sparse_conv_t h, int N, int H, int W, int stride, int
  * host side if needed; needs no GPU.  params must have room for 16 ints. */
 int sparse_conv_get_launch(sparse_conv_t h, int N, int H, int W, int stride, int pad, int* params);
 
+/*
+ * Roof probes: kernels of known work, for measuring on the machine at hand the two rates the
+ * benchmark's roofline fractions refer to (the caller times them with events on `stream`).
+ * sparse_conv_probe_lds_read: `workgroups` workgroups of 1024 threads; every wavefront reads 64
+ *   consecutive 16-byte LDS elements (ds_read_b128, the gather pattern of section 8's multiply loop
+ *   as this library lays it out) 8 * iterations times and does nothing else.  sink: DEVICE, at least
+ *   4096 * workgroups bytes (one float per thread is written so that the reads are kept).
+ *   *bytes_read receives the LDS bytes read by the whole launch.
+ * sparse_conv_probe_copy: copies bytes / 16 16-byte words from src to dst (DEVICE, 16-byte aligned,
+ *   not overlapping): `bytes` read and `bytes` written, the traffic of a plain copy.
+ * Both return SC_EINVAL for bad arguments, SC_EHIP if the launch failed.
+ */
+int sparse_conv_probe_lds_read(void* sink, int workgroups, int iterations, void* stream, long long* bytes_read);
+int sparse_conv_probe_copy(void* dst, const void* src, long long bytes, void* stream);
+
 /* HIP error code of the last failing runtime call made through this handle (0 if none). */
 int sparse_conv_last_hip_error(sparse_conv_t h);
 

@@ -27,6 +27,7 @@ EXPORTS = (
     "sparse_conv_create", "sparse_conv_output_shape", "sparse_conv_forward", "sparse_conv_forward_static",
     "sparse_conv_get_csr", "sparse_conv_set_launch", "sparse_conv_get_launch", "sparse_conv_set_epilogue", "sparse_conv_autotune",
     "sparse_conv_create_codebook", "sparse_conv_get_codebook", "sparse_conv_check_plan", "sparse_conv_rank_launches",
+    "sparse_conv_probe_lds_read", "sparse_conv_probe_copy",
     "sparse_conv_last_hip_error", "sparse_conv_strerror", "sparse_conv_destroy",
 )
 
@@ -65,6 +66,8 @@ def _load():
     lib.sparse_conv_rank_launches.argtypes = [vp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, ip, ip]
     lib.sparse_conv_autotune.argtypes = [vp, vp, vp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, vp, C.c_int,
                                          C.POINTER(C.c_float)]
+    lib.sparse_conv_probe_lds_read.argtypes = [vp, C.c_int, C.c_int, vp, C.POINTER(C.c_longlong)]
+    lib.sparse_conv_probe_copy.argtypes = [vp, vp, C.c_longlong, vp]
     lib.sparse_conv_last_hip_error.argtypes = [vp]
     lib.sparse_conv_strerror.argtypes = [C.c_int]
     lib.sparse_conv_strerror.restype = C.c_char_p
@@ -212,6 +215,19 @@ def sparse_conv_check_plan(handle: int, N: int, H: int, W: int, stride: int, pad
     bad = C.c_int(-1)
     _check(_lib.sparse_conv_check_plan(handle, N, H, W, stride, pad, C.byref(bad)), "sparse_conv_check_plan", handle)
     return int(bad.value)
+
+
+def sparse_conv_probe_lds_read(sink_ptr: int, workgroups: int, iterations: int, stream: int = 0) -> int:
+    """Enqueues the LDS read probe; returns the LDS bytes the launch reads."""
+    n = C.c_longlong(0)
+    _check(_lib.sparse_conv_probe_lds_read(sink_ptr, workgroups, iterations, stream or None, C.byref(n)),
+           "sparse_conv_probe_lds_read")
+    return int(n.value)
+
+
+def sparse_conv_probe_copy(dst_ptr: int, src_ptr: int, nbytes: int, stream: int = 0) -> None:
+    """Enqueues the copy probe (nbytes read, nbytes written)."""
+    _check(_lib.sparse_conv_probe_copy(dst_ptr, src_ptr, nbytes, stream or None), "sparse_conv_probe_copy")
 
 
 def sparse_conv_destroy(handle: Optional[int]) -> None:

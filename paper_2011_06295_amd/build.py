@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsparseconv.so")
-SOURCES = ["kernels.hip", "api.cpp", "plan.cpp", "host_csr.cpp"]
+SOURCES = ["kernels.hip", "probes.hip", "api.cpp", "plan.cpp", "host_csr.cpp"]
 
 # packed fp32 VALU forms are switched off for the device pass (the host pass
 # prints a harmless "not a recognized feature" note for the same flag)

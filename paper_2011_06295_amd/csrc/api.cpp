@@ -611,6 +611,18 @@ int sparse_conv_check_plan(sparse_conv_t h, int N, int H, int W, int stride, int
     }
 }
 
+int sparse_conv_probe_lds_read(void* sink, int workgroups, int iterations, void* stream, long long* bytes_read)
+{
+    if (!sink || workgroups <= 0 || workgroups > (1 << 16) || iterations <= 0) return SC_EINVAL;
+    return sc::launch_lds_read_probe(sink, workgroups, iterations, stream, bytes_read) == 0 ? SC_OK : SC_EHIP;
+}
+
+int sparse_conv_probe_copy(void* dst, const void* src, long long bytes, void* stream)
+{
+    if (!dst || !src || bytes < 16 || dst == src) return SC_EINVAL;
+    return sc::launch_copy_probe(dst, src, bytes, stream) == 0 ? SC_OK : SC_EHIP;
+}
+
 int sparse_conv_last_hip_error(sparse_conv_t h) { return h ? h->last_hip : 0; }
 
 const char* sparse_conv_strerror(int code)

@@ -214,6 +214,10 @@ int static_scratch(void** ptr);
 int launch_tile_kernel(int dtype, int V, int KW, int LP, const KernelArgs& a, int grid, int threads,
                        int lds_bytes, void* stream);
 
+// Roof probes (probes.hip).  Each enqueues one kernel and returns a hipError_t value.
+int launch_lds_read_probe(void* sink, int workgroups, int iterations, void* stream, long long* bytes_read);
+int launch_copy_probe(void* dst, const void* src, long long bytes, void* stream);
+
 }  // namespace sc
 
 struct sparse_conv_s {

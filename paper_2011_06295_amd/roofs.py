@@ -1,0 +1,19 @@
+"""Roofs the benchmark's fractions are quoted against: MI355X's published peaks, and beside them the
+rates measured on this machine with the library's own probe kernels (`bench.py --probe`; the run behind
+the figures below is kept in profiles/roof_probes.md)."""
+
+CUS = 256
+CLOCK_HZ = 2.4e9
+
+# published
+HBM_PEAK = 8.0e12                              # B/s
+LDS_PEAK = CUS * 256 * CLOCK_HZ                # 256 B/clk/CU for wide LDS reads: 157.3 TB/s
+VALU_PEAK_FMA = CUS * 64 * CLOCK_HZ            # non-packed fp32 multiply-adds per second: 4 SIMDs x 16 lanes per CU
+                                               # (78.6 TFLOP/s; the 157.3 TFLOP/s datasheet figure is the packed form,
+                                               # which this build does not use)
+VALU_PEAK_FMA_PACKED = 2 * VALU_PEAK_FMA
+
+# measured with `bench.py --probe` (profiles/roof_probes.md)
+MEASURED_LDS_B_PER_CLK_PER_CU = 229.4          # ds_read_b128, 64 consecutive elements per wavefront, 16 wavefronts per CU
+MEASURED_COPY_BYTES_PER_S = 4.62e12            # read + write bytes of a 1 GiB copy
+PROFILE = "profiles/roof_probes.md"
