@@ -134,6 +134,10 @@ def main():
                     help="1: the default workload's line also carries `configs`, the other benchmark configurations "
                          "(vgg16_f16, the 14x14 layer at 90/95/99 %% and with ragged rows, lenet5, config1), each tuned and "
                          "timed by the same protocol; 0: the one workload only")
+    ap.add_argument("--tuning-table", default="",
+                    help="JSON file keyed by layer geometry (dtype,N,C,H,W,K,R,S,stride,pad,nnz): if it exists and knows "
+                         "every layer, their launch configurations (and dense/sparse routes) are pinned from it instead of "
+                         "being measured again; after the run the table is written back with what was used")
     ap.add_argument("--probe", action="store_true",
                     help="measure the roofs instead of a workload: LDS read rate of the gather's access pattern and the "
                          "rate of a plain copy, with the library's probe kernels; prints one JSON line")
@@ -243,6 +247,10 @@ def run_workload(name, args, steps, warmup, brief):
     b = 2 if work.dtype == "f16" else 4
     pinned = [int(v) for v in args.launch.split(",")] if args.launch else []
     tune = args.autotune > 0 and not all(pinned[:4] + [len(pinned) >= 4])   # a launch shape given in full is taken as it is
+    known = 0
+    if args.tuning_table and os.path.exists(args.tuning_table) and not args.launch:
+        known = net.load_table(args.tuning_table)      # launches (and routes) measured by an earlier run
+        tune = tune and known < len(net.runs)
     if tune:
         net.autotune(args.autotune)
 
@@ -350,7 +358,7 @@ def run_workload(name, args, steps, warmup, brief):
                    "layers": nl, "batch": N, "total_macs": total_macs,
                    "launch": ((f"override {args.launch}; " if args.launch else "") +
                               (f"measured best of {args.autotune} ranked candidates per layer" + (", re-checked inside a pass" if args.refine else "") if tune
-                               else "cost estimate"))},
+                               else f"pinned from {args.tuning_table}" if known else "cost estimate"))},
         "roofline": roofline,
         "layers": layers,
     }
@@ -361,10 +369,16 @@ def run_workload(name, args, steps, warmup, brief):
         out["config"]["kept_weights"] = sum(int(m.sum()) for _, m in net.host_weights)
     if args.compare_dense:
         rows = net.compare_with_dense()
+        # the routed pass is run and timed as one loop, like the all-sparse one beside it
         out["dense_comparison"] = {"layers": rows,
                                    "sparse_us": round(sum(r["sparse_us"] for r in rows), 1),
                                    "dense_us": round(sum(r["dense_us"] for r in rows), 1),
-                                   "dispatched_us": round(sum(min(r["sparse_us"], r["dense_us"]) for r in rows), 1)}
+                                   "routes": list(net.route),
+                                   "sparse_pass_us": round(net.time_pass(False), 1),
+                                   "dispatched_pass_us": round(net.time_pass(True), 1)}
+    if args.tuning_table:
+        net.save_table(args.tuning_table)
+        out["config"]["tuning_table"] = args.tuning_table
     if not args.no_cpu:
         # the outputs the oracle looks at are those of a pass with the timed launches over the first buffer set
         for r in net.runs:

@@ -6,7 +6,9 @@ part of the sparse kernel of section 8) are plain torch ops on the same stream.
 """
 from __future__ import annotations
 
-from typing import List, Optional
+import json
+import os
+from typing import Dict, List, Optional
 
 import numpy as np
 
@@ -43,6 +45,12 @@ class Network:
             rowptr = layer.csr()[0]
             self.runs.append(LayerRun(spec, layer, int(rowptr[-1])))
             self.host_weights.append((w, m))
+        # per layer: "sparse" (this library) or "dense" (the platform's dense convolution on the masked weights);
+        # filled by compare_with_dense or load_table, honoured by step(dispatch=True) / run_chain(dispatch=True)
+        self.route: List[str] = ["sparse"] * len(self.runs)
+        self._dense_w = [None] * len(self.runs)
+        self._dense_out = [None] * len(self.runs)
+        self.timings: Dict[int, dict] = {}
 
     def torch_dtype(self):
         import torch
@@ -58,8 +66,67 @@ class Network:
             y = F.max_pool2d(y, 2)
         return y.contiguous()
 
-    def run_chain(self, x0: np.ndarray):
-        """Pushes x0 through every layer once, keeping each layer's input and output on the device."""
+    # ------------------------------------------------------------ routing (the paper's Algorithm 2)
+
+    def _dense_weights(self, li: int):
+        import torch
+        if self._dense_w[li] is None:
+            w, m = self.host_weights[li]
+            self._dense_w[li] = torch.from_numpy(w * m).cuda().to(self.torch_dtype())
+        return self._dense_w[li]
+
+    def forward_layer(self, li: int, x, y=None, dispatch: bool = False):
+        """One layer on x: the sparse kernel (into y if given), or, with dispatch and a "dense" route, the
+        platform's dense convolution on the masked weights (its own output tensor)."""
+        import torch.nn.functional as F
+        run = self.runs[li]
+        s = run.spec
+        if dispatch and self.route[li] == "dense":
+            self._dense_out[li] = F.conv2d(x, self._dense_weights(li), None, s.stride, s.pad)
+            return self._dense_out[li]
+        return run.layer.forward(x, s.stride, s.pad, out=y)
+
+    def table_key(self, li: int) -> str:
+        s = self.runs[li].spec
+        return ",".join(str(v) for v in (self.work.dtype, self.work.N, s.C, s.H, s.W, s.K, s.R, s.S, s.stride, s.pad,
+                                         self.runs[li].nnz))
+
+    def save_table(self, path: str) -> dict:
+        """Writes (merging with what the file holds) per layer geometry: the route the comparison picked, the
+        launch configuration in force, and the measured times.  Key: dtype,N,C,H,W,K,R,S,stride,pad,nnz."""
+        table = {}
+        if os.path.exists(path):
+            with open(path) as f:
+                table = json.load(f)
+        for li, run in enumerate(self.runs):
+            s = run.spec
+            d = run.layer.get_launch(self.work.N, s.H, s.W, s.stride, s.pad)
+            entry = {"route": self.route[li],
+                     "launch": [d["V"], d["WP"], d["WK"], d["KW"], d["Cc"], 0, d["LP"], d["kblocks"], d["store"], d["lanes"],
+                                d["csplit"]]}
+            entry.update(self.timings.get(li, {}))
+            table[self.table_key(li)] = entry
+        with open(path, "w") as f:
+            json.dump(table, f, indent=1, sort_keys=True)
+        return table
+
+    def load_table(self, path: str) -> int:
+        """Pins route and launch configuration of every layer the table knows; returns how many it knew."""
+        with open(path) as f:
+            table = json.load(f)
+        known = 0
+        for li, run in enumerate(self.runs):
+            entry = table.get(self.table_key(li))
+            if entry is None:
+                continue
+            run.layer.set_launch(entry["launch"])
+            self.route[li] = entry.get("route", "sparse")
+            known += 1
+        return known
+
+    def run_chain(self, x0: np.ndarray, dispatch: bool = False):
+        """Pushes x0 through every layer once, keeping each layer's input and output on the device
+        (dispatch: every layer through the implementation its route names)."""
         import torch
         x = torch.from_numpy(x0).cuda().to(self.torch_dtype()).contiguous()
         for li, run in enumerate(self.runs, 1):
@@ -68,7 +135,7 @@ class Network:
                 xi = wl.make_layer_input(self.work.config, lid, run.spec, self.work.N, self.work.input_dist)
                 x = torch.from_numpy(xi).cuda().to(self.torch_dtype()).contiguous()
             run.x = x
-            run.y = run.layer.forward(x, run.spec.stride, run.spec.pad)
+            run.y = self.forward_layer(li - 1, x, None, dispatch)
             x = self.glue(run.spec, run.y)
         torch.cuda.synchronize()
         return x
@@ -136,13 +203,18 @@ class Network:
         torch.cuda.synchronize()
         return nsets
 
-    def step(self, which: int = 0):
+    def step(self, which: int = 0, dispatch: bool = False):
         """One pass of the hot path: every layer's convolution on its resident input
-        (buffer set `which`, modulo the number of sets, once make_buffer_sets has run)."""
+        (buffer set `which`, modulo the number of sets, once make_buffer_sets has run).
+        dispatch: layers routed to the dense implementation run there instead."""
         sets = getattr(self, "sets", None)
         bufs = sets[which % len(sets)] if sets else [(r.x, r.y) for r in self.runs]
-        for run, (x, y) in zip(self.runs, bufs):
-            run.layer.forward(x, run.spec.stride, run.spec.pad, out=y)
+        if not dispatch:
+            for run, (x, y) in zip(self.runs, bufs):
+                run.layer.forward(x, run.spec.stride, run.spec.pad, out=y)
+            return
+        for li, (x, y) in enumerate(bufs):
+            self.forward_layer(li, x, y, True)
 
     def compare_with_dense(self, reps: int = 20):
         """Per layer: time of the sparse kernel and of the platform's dense convolution
@@ -153,9 +225,9 @@ class Network:
         import torch
         import torch.nn.functional as F
         out = []
-        for (w, m), run in zip(self.host_weights, self.runs):
+        for li, ((w, m), run) in enumerate(zip(self.host_weights, self.runs)):
             s = run.spec
-            wd = torch.from_numpy(w * m).cuda().to(self.torch_dtype())
+            wd = self._dense_weights(li)
             yd = F.conv2d(run.x, wd, None, s.stride, s.pad)
             ys = run.layer.forward(run.x, s.stride, s.pad, out=run.y)
             diff = float((yd.float() - ys.float()).abs().max())
@@ -171,12 +243,27 @@ class Network:
                 z.record()
                 torch.cuda.synchronize()
                 times[name] = a.elapsed_time(z) * 1e3 / reps
+            choice = "sparse" if times["sparse"] <= times["dense"] else "dense"
+            self.route[li] = choice
+            self.timings[li] = {"sparse_us": round(times["sparse"], 2), "dense_us": round(times["dense"], 2)}
             out.append({"name": s.name, "sparsity": s.sparsity_bp / 100.0, "sparse_us": round(times["sparse"], 2),
-                        "dense_us": round(times["dense"], 2),
-                        "choice": "sparse" if times["sparse"] <= times["dense"] else "dense",
-                        "max_abs_diff": diff})
-            del wd, yd
+                        "dense_us": round(times["dense"], 2), "choice": choice, "max_abs_diff": diff})
+            del yd
         return out
+
+    def time_pass(self, dispatch: bool, steps: int = 20, warmup: int = 3) -> float:
+        """us per pass over the buffer sets in rotation, every layer through its route (dispatch) or all sparse."""
+        import torch
+        for i in range(warmup):
+            self.step(i, dispatch)
+        torch.cuda.synchronize()
+        a, z = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for i in range(steps):
+            self.step(i, dispatch)
+        z.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(z) * 1e3 / steps
 
     def total_macs(self) -> int:
         return sum(r.macs(self.work.N) for r in self.runs)
