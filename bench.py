@@ -134,6 +134,9 @@ def main():
                     help="1: the default workload's line also carries `configs`, the other benchmark configurations "
                          "(vgg16_f16, the 14x14 layer at 90/95/99 %% and with ragged rows, lenet5, config1), each tuned and "
                          "timed by the same protocol; 0: the one workload only")
+    ap.add_argument("--codebook", action="store_true",
+                    help="cluster-quantised layers: weights given as 4-bit centroid numbers into 16 binary16 centroids "
+                         "(the device entries are 4 bytes instead of 8)")
     ap.add_argument("--tuning-table", default="",
                     help="JSON file keyed by layer geometry (dtype,N,C,H,W,K,R,S,stride,pad,nnz): if it exists and knows "
                          "every layer, their launch configurations (and dense/sparse routes) are pinned from it instead of "
@@ -174,7 +177,7 @@ def main():
         print(json.dumps(probe_roofs()))
         return
     out = run_workload(args.workload, args, args.steps, args.warmup, brief=False)
-    if args.configs and args.workload == "vgg16_f32" and not args.launch and not args.unify:
+    if args.configs and args.workload == "vgg16_f32" and not args.launch and not args.unify and not args.codebook:
         # the other benchmark configurations, each tuned and timed by the same protocol (fewer steps, no
         # per-layer table, no CPU timing; the sampled comparison with the oracle stays)
         out["configs"] = []
@@ -238,7 +241,7 @@ def run_workload(name, args, steps, warmup, brief):
     from paper_2011_06295_amd import harness, workloads as wl
 
     work, layer_ids = make_workload(name)
-    net = harness.Network(work, unify=args.unify, layer_ids=layer_ids)
+    net = harness.Network(work, unify=args.unify, layer_ids=layer_ids, codebook=args.codebook)
     if args.launch:
         for r in net.runs:
             r.layer.set_launch([int(v) for v in args.launch.split(",")])
@@ -353,7 +356,7 @@ def run_workload(name, args, steps, warmup, brief):
         "ms_per_step": ms_per_step, "gpu_ms_per_step": gpu_ms / steps,
         "cache_hot_ms_per_step": hot_wall * 1e3 / steps, "buffer_sets": nsets,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": work.dtype, "data": "synthetic",
+        "dtype": work.dtype, "data": "synthetic" + (", cluster-quantised weights (4-bit numbers, 16 centroids)" if args.codebook else ""),
         "config": {"workload": f"{work.name}, batch {N}, {nl} sparse conv layer(s), conv only, inputs resident in HBM, {nsets} buffer set(s) in rotation",
                    "layers": nl, "batch": N, "total_macs": total_macs,
                    "launch": ((f"override {args.launch}; " if args.launch else "") +

@@ -157,8 +157,10 @@ int sparse_conv_get_csr(sparse_conv_t h, int* K, long long* nnz,
  * CSR order, two to a byte (entry 2i in the low nibble of byte i, entry 2i+1 in the
  * high nibble, an unused last nibble zero) and the 16 centroids: 0.5 byte per
  * stored weight instead of 2 or 4.  sparse_conv_get_csr returns the decoded
- * values.  The device plan is built from the decoded values, so the forward
- * path and its launch configuration do not differ from an uncoded layer's.
+ * values.  On the device a plan entry of such a layer is one 32-bit word (LDS offset
+ * in 16 bits and the centroid itself as binary16) instead of the 8-byte (fp32 weight,
+ * offset) pair: half the stream the kernel fetches, for SC_F32 layers too; the
+ * multiply-add takes the binary16 weight as it is (mixed precision, fp32 sum).
  * SC_EINVAL: bad arguments, an index above 15 under the mask, or explicit zeros
  * are needed and no centroid is zero.
  */
@@ -265,7 +267,9 @@ int sparse_conv_check_plan(sparse_conv_t h, int N, int H, int W, int stride, int
  * per workgroup, [8] threads per workgroup, [9] stored plan entries
  * (including batch padding), [10] LP, [11] channel blocks, [12] kind of output store
  * (1 or 2), [13] what a lane stands for (1, or 1 + G, as sparse_conv_set_launch takes it),
- * [14] workgroups the channels are dealt over, [15] reserved (0).  [0..5] are in the order of sparse_conv_set_launch.  Builds the plan's
+ * [14] workgroups the channels are dealt over, [15] bytes per plan entry on the device (8: fp32 weight
+ * and LDS offset; 4: binary16 weight and 16-bit LDS offset, for SC_F16 handles and handles made by
+ * sparse_conv_create_codebook).  [0..5] are in the order of sparse_conv_set_launch.  Builds the plan's
  * host side if needed; needs no GPU.  params must have room for 16 ints. */
 int sparse_conv_get_launch(sparse_conv_t h, int N, int H, int W, int stride, int pad, int* params);
 

@@ -197,7 +197,7 @@ def sparse_conv_get_launch(handle: int, N: int, H: int, W: int, stride: int, pad
     arr = (C.c_int * 16)()
     _check(_lib.sparse_conv_get_launch(handle, N, H, W, stride, pad, arr), "sparse_conv_get_launch", handle)
     names = ("V", "WP", "WK", "KW", "Cc", "lds_budget", "grid", "lds_bytes", "threads", "entries", "LP", "kblocks", "store",
-             "lanes", "csplit")
+             "lanes", "csplit", "entry_bytes")
     return dict(zip(names, list(arr)))
 
 

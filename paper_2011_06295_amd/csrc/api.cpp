@@ -113,6 +113,16 @@ int upload(sparse_conv_s* h, const std::vector<T>& v, void** dst)
 // The entry table as the device reads it: per batch the weights, then the offsets two to a word.
 void build_image(Plan& p)
 {
+    if (p.compact) {   // one word per entry: LDS offset in its unit and the weight as binary16 (exact: it is one)
+        if (!p.image4.empty()) return;
+        p.image4.resize(p.entries.size());
+        for (size_t i = 0; i < p.entries.size(); ++i) {
+            float wv;
+            std::memcpy(&wv, &p.entries[i].wbits, 4);
+            p.image4[i] = ((uint32_t)(p.entries[i].off >> p.off_shift) << 16) | float_to_half_rne(wv);
+        }
+        return;
+    }
     if (!p.image.empty() || p.entries.empty()) return;
     p.image.resize(p.entries.size() / kBatch);
     for (size_t b = 0; b < p.image.size(); ++b)
@@ -130,6 +140,8 @@ void fill_args(const sparse_conv_s* h, const Plan* p, const void* input, void* o
     a.x = input;
     a.y = output;
     a.bias = h->d_bias;
+    a.compact = p->compact ? 1 : 0;
+    a.off_shift = p->off_shift;
     a.relu = (h->epilogue & SC_EPILOGUE_RELU) ? 1 : 0;
     a.nt_store = p->store == 2 ? 1 : 0;
     a.N = N; a.C = h->C; a.H = H; a.W = W; a.K = h->K; a.E = p->E; a.F = p->F;
@@ -215,7 +227,8 @@ int forward_impl(sparse_conv_s* h, const void* input, void* output, int N, int H
         if (!use_static) {
             if (!p->uploaded) {
                 build_image(*p);
-                if ((rc = upload(h, p->image, &p->d_entries)) != SC_OK) return rc;
+                if ((rc = p->compact ? upload(h, p->image4, &p->d_entries) : upload(h, p->image, &p->d_entries)) != SC_OK)
+                    return rc;
                 if ((rc = upload(h, p->seg, &p->d_seg)) != SC_OK) return rc;
                 if ((rc = upload(h, p->krow, &p->d_krow)) != SC_OK) return rc;
                 if (p->J > 1) {
@@ -243,8 +256,9 @@ int forward_impl(sparse_conv_s* h, const void* input, void* output, int N, int H
             a.counters = static_cast<unsigned*>(p->d_counters);
         } else {
             build_image(*p);
-            const size_t b_entries = p->image.size() * sizeof(Batch), b_seg = p->seg.size() * sizeof(int),
-                         b_krow = p->krow.size() * sizeof(int);
+            const size_t b_entries = p->compact ? p->image4.size() * sizeof(uint32_t) : p->image.size() * sizeof(Batch),
+                         b_seg = p->seg.size() * sizeof(int), b_krow = p->krow.size() * sizeof(int);
+            const void* entries_at = p->compact ? static_cast<const void*>(p->image4.data()) : static_cast<const void*>(p->image.data());
             const size_t at_seg = round256(b_entries), at_krow = at_seg + round256(b_seg);
             const size_t at_counters = at_krow + round256(b_krow), at_partial = at_counters + round256(counter_bytes(*p));
             if (at_partial + partial_bytes(*p) > kStaticScratchBytes) return SC_ETOOBIG;
@@ -260,7 +274,7 @@ int forward_impl(sparse_conv_s* h, const void* input, void* output, int N, int H
             if (holds != p->id) {
                 holds = 0;
                 hipStream_t s = static_cast<hipStream_t>(stream);
-                hipError_t he = hipMemcpyAsync(d, p->image.data(), b_entries, hipMemcpyHostToDevice, s);
+                hipError_t he = hipMemcpyAsync(d, entries_at, b_entries, hipMemcpyHostToDevice, s);
                 if (he == hipSuccess) he = hipMemcpyAsync(d + at_seg, p->seg.data(), b_seg, hipMemcpyHostToDevice, s);
                 if (he == hipSuccess) he = hipMemcpyAsync(d + at_krow, p->krow.data(), b_krow, hipMemcpyHostToDevice, s);
                 // the counters start at zero (every launch leaves them there); whatever the array held before goes
@@ -434,7 +448,7 @@ int sparse_conv_get_launch(sparse_conv_t h, int N, int H, int W, int stride, int
         if (rc != SC_OK) return rc;
         const int v[16] = {p->V, p->WP, p->WK, p->KW, p->Cc, h->over.lds_budget,
                            p->grid, p->lds_bytes, p->threads, (int)p->entries.size(), p->LP, p->kblocks, p->store,
-                           1 + p->G, p->J, 0};
+                           1 + p->G, p->J, p->compact ? 4 : 8};
         std::memcpy(params, v, sizeof(v));
         return SC_OK;
     } catch (...) {

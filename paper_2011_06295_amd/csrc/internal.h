@@ -133,6 +133,9 @@ struct Plan {
     int lds_bytes; // tile + slot table
     int grid;      // workgroups launched (ntiles * kblocks rounded up to the XCD count)
     // host tables
+    bool compact = false;         // binary16 weights (binary16 layers, cluster-quantised layers): one word per device entry
+    int off_shift = 0;            // compact: LDS byte offset = (entry >> 16) << off_shift
+    std::vector<uint32_t> image4; // compact: the entry table as the device reads it, (offset >> off_shift) << 16 | binary16 weight
     std::vector<Entry> entries;   // segments padded to kBatch
     std::vector<int> seg;         // [kblocks][nchunks][WK][1 + KW] = first entry, batches of each row; then one
                                   // terminal descriptor whose first entry is the end of the last segment
@@ -171,7 +174,9 @@ FastDiv make_fastdiv(int d);
 struct KernelArgs {
     const void* x;
     void* y;
-    const uint32_t* entries;   // device image: one Batch per kBatch entries
+    const uint32_t* entries;   // device image: one Batch per kBatch entries (compact: one 32-bit word per entry)
+    int compact;               // entries are (offset units << 16 | binary16 weight) words
+    int off_shift;             // compact: bytes per offset unit, as a shift (1 or 2)
     const int* seg;
     const int* krow;
     const float* bias;   // [K] or null

@@ -139,7 +139,7 @@ struct Vec<T, 1> {
     } while (0)
 #endif
 
-template <typename T, int V, int KW, int LP>
+template <typename T, int V, int KW, int LP, bool COMPACT>
 __global__ __launch_bounds__(1024) void tile_kernel(const KernelArgs a)
 {
 #ifdef SC_PHASE_TIMING
@@ -245,18 +245,47 @@ __global__ __launch_bounds__(1024) void tile_kernel(const KernelArgs a)
     int d_nb[KW];
 #pragma unroll
     for (int kk = 0; kk < KW; ++kk) d_nb[kk] = sg[1 + kk];
-    const SC_CONSTANT uint32_t* e = nullptr;   // 2 * kBatch dwords per batch
+    // Compact entries (binary16 layers, and cluster-quantised layers, whose weights are binary16 centroids:
+    // sections 6 and 9): an entry is one word, (LDS offset in units of 2 or 4 bytes) << 16 | binary16 weight,
+    // half the bytes of the (fp32 weight, offset) pair.  A batch is decoded once, when it has arrived, on the
+    // scalar unit: the offsets are shifted into the places an ordinary batch has them in; the weight stays
+    // where it is and goes into the mixed-precision multiply-add as a binary16 operand (no conversion).
+    // (A 4-bit centroid number in the entry and a table lookup per entry were measured, with the table in
+    // a register (v_readlane) and in the scalar cache (dependent s_load): both a third slower.)
+    constexpr bool compact = COMPACT;
+    constexpr int epd = compact ? 1 : 2;       // 32-bit words per entry
+    const SC_CONSTANT uint32_t* e = nullptr;   // epd * kBatch dwords per batch
     int nb[KW];
     Batch cur;
-    auto fetch_batch = [](Batch& b, const SC_CONSTANT uint32_t* p) __attribute__((always_inline)) {
+    auto fetch_batch = [&](Batch& b, const SC_CONSTANT uint32_t* p) __attribute__((always_inline)) {
 #pragma unroll
         for (int u = 0; u < kBatch; ++u) b.w[u] = p[u];
-        const SC_CONSTANT unsigned long long* q = reinterpret_cast<const SC_CONSTANT unsigned long long*>(p + kBatch);
+        if constexpr (!compact) {
+            const SC_CONSTANT unsigned long long* q = reinterpret_cast<const SC_CONSTANT unsigned long long*>(p + kBatch);
 #pragma unroll
-        for (int u = 0; u < kBatch / 2; ++u) b.off2[u] = q[u];
+            for (int u = 0; u < kBatch / 2; ++u) b.off2[u] = q[u];
+        }
+    };
+    auto decode = [&](Batch& b) __attribute__((always_inline)) {
+        if constexpr (!compact) return;
+#pragma unroll
+        for (int u = 0; u < kBatch / 2; ++u)
+            b.off2[u] = ((unsigned long long)((b.w[2 * u + 1] >> 16) << a.off_shift) << 32) |
+                        (unsigned long long)((b.w[2 * u] >> 16) << a.off_shift);
+    };
+    // the weight of an entry as the multiply-add takes it
+    auto weight = [](uint32_t word) __attribute__((always_inline)) -> float {
+        if constexpr (compact) {
+            const unsigned short h = (unsigned short)word;
+            _Float16 f;
+            __builtin_memcpy(&f, &h, 2);
+            return (float)f;
+        } else {
+            return __uint_as_float(word);
+        }
     };
     auto begin_chunk = [&](int ch) __attribute__((always_inline)) {
-        e = as_constant(a.entries) + 2 * (size_t)d_start;
+        e = as_constant(a.entries) + (size_t)epd * (size_t)d_start;
 #pragma unroll
         for (int kk = 0; kk < KW; ++kk) nb[kk] = d_nb[kk];
         fetch_batch(cur, e);  // the table ends in kBatch slack entries
@@ -273,8 +302,8 @@ __global__ __launch_bounds__(1024) void tile_kernel(const KernelArgs a)
     // 64 bytes of the coming segment (d_start..d_end), issued a chunk ahead, brings the lines
     // into L2 first.  The loaded value is only kept until the next wait for staged data.
     auto touch = [&]() __attribute__((always_inline)) -> unsigned {
-        const int first = d_start + lane * 8;  // 8 entries = 64 bytes
-        return first < d_end ? a.entries[2 * (size_t)first] : 0u;
+        const size_t first = (size_t)epd * (size_t)d_start + (size_t)lane * 16;  // 16 words = 64 bytes
+        return first < (size_t)epd * (size_t)d_end ? a.entries[first] : 0u;
     };
     auto retire = [](unsigned t) __attribute__((always_inline)) { asm volatile("" ::"v"(t)); };
 
@@ -453,13 +482,14 @@ __global__ __launch_bounds__(1024) void tile_kernel(const KernelArgs a)
         auto fma = [&](const vec(&x)[kGroup][LP], const Batch& E, int g, float (&ac)[LP][V]) __attribute__((always_inline)) {
 #pragma unroll
             for (int u = 0; u < kGroup; ++u) {
-                const float w = __uint_as_float(E.w[g * kGroup + u]);
+                const float w = weight(E.w[g * kGroup + u]);
 #pragma unroll
                 for (int p = 0; p < LP; ++p)
 #pragma unroll
                     for (int v = 0; v < V; ++v) ac[p][v] = __builtin_fmaf(w, (float)VT::get(x[u][p], v), ac[p][v]);
             }
         };
+        decode(cur);
         gather(xs[0], cur, 0);
         arrived(xs[0]);
         // A step consumes batch A group by group: while the multiply-adds of group j run on one
@@ -471,11 +501,12 @@ __global__ __launch_bounds__(1024) void tile_kernel(const KernelArgs a)
                 __builtin_amdgcn_sched_barrier(0);
                 if (j == 0) {
                     gather(xs[1], A, 1);
-                    e += 2 * kBatch;
+                    e += epd * kBatch;
                     fetch_batch(B, e);
                 } else if (j + 1 < kGroups) {
                     gather(xs[(j + 1) & 1], A, j + 1);
                 } else {
+                    decode(B);   // complete since the wait that ended the first group
                     gather(xs[0], B, 0);
                 }
                 __builtin_amdgcn_sched_barrier(0);
@@ -654,14 +685,14 @@ __global__ __launch_bounds__(1024) void tile_kernel(const KernelArgs a)
 
 namespace {
 
-template <typename T, int V, int KW, int LP>
+template <typename T, int V, int KW, int LP, bool COMPACT>
 int launch_one(const KernelArgs& a, int grid, int threads, int lds_bytes, hipStream_t s)
 {
     // accumulators (KW * LP * V floats) plus the reads in flight have to fit a 128-register wavefront
     if constexpr ((LP > 1 && KW * LP * V > 32) || KW * V > 64) {
         return (int)hipErrorInvalidValue;
     } else {
-    auto fn = tile_kernel<T, V, KW, LP>;
+    auto fn = tile_kernel<T, V, KW, LP, COMPACT>;
     if (lds_bytes > 64 * 1024) {
         // more than 64 KB of dynamic LDS has to be allowed per kernel and device: once, for the whole 160 KB
         static std::atomic<unsigned long long> allowed{0};   // one bit per device ordinal
@@ -685,15 +716,15 @@ template <typename T, int V>
 int launch_kw(int KW, int LP, const KernelArgs& a, int grid, int threads, int lds, hipStream_t s)
 {
     switch (KW * 8 + LP) {
-        case 1 * 8 + 1: return launch_one<T, V, 1, 1>(a, grid, threads, lds, s);
-        case 2 * 8 + 1: return launch_one<T, V, 2, 1>(a, grid, threads, lds, s);
-        case 4 * 8 + 1: return launch_one<T, V, 4, 1>(a, grid, threads, lds, s);
-        case 8 * 8 + 1: return launch_one<T, V, 8, 1>(a, grid, threads, lds, s);
-        case 16 * 8 + 1: return launch_one<T, V, 16, 1>(a, grid, threads, lds, s);
-        case 1 * 8 + 2: return launch_one<T, V, 1, 2>(a, grid, threads, lds, s);
-        case 2 * 8 + 2: return launch_one<T, V, 2, 2>(a, grid, threads, lds, s);
-        case 4 * 8 + 2: return launch_one<T, V, 4, 2>(a, grid, threads, lds, s);
-        case 8 * 8 + 2: return launch_one<T, V, 8, 2>(a, grid, threads, lds, s);
+        case 1 * 8 + 1: return a.compact ? launch_one<T, V, 1, 1, true>(a, grid, threads, lds, s) : launch_one<T, V, 1, 1, false>(a, grid, threads, lds, s);
+        case 2 * 8 + 1: return a.compact ? launch_one<T, V, 2, 1, true>(a, grid, threads, lds, s) : launch_one<T, V, 2, 1, false>(a, grid, threads, lds, s);
+        case 4 * 8 + 1: return a.compact ? launch_one<T, V, 4, 1, true>(a, grid, threads, lds, s) : launch_one<T, V, 4, 1, false>(a, grid, threads, lds, s);
+        case 8 * 8 + 1: return a.compact ? launch_one<T, V, 8, 1, true>(a, grid, threads, lds, s) : launch_one<T, V, 8, 1, false>(a, grid, threads, lds, s);
+        case 16 * 8 + 1: return a.compact ? launch_one<T, V, 16, 1, true>(a, grid, threads, lds, s) : launch_one<T, V, 16, 1, false>(a, grid, threads, lds, s);
+        case 1 * 8 + 2: return a.compact ? launch_one<T, V, 1, 2, true>(a, grid, threads, lds, s) : launch_one<T, V, 1, 2, false>(a, grid, threads, lds, s);
+        case 2 * 8 + 2: return a.compact ? launch_one<T, V, 2, 2, true>(a, grid, threads, lds, s) : launch_one<T, V, 2, 2, false>(a, grid, threads, lds, s);
+        case 4 * 8 + 2: return a.compact ? launch_one<T, V, 4, 2, true>(a, grid, threads, lds, s) : launch_one<T, V, 4, 2, false>(a, grid, threads, lds, s);
+        case 8 * 8 + 2: return a.compact ? launch_one<T, V, 8, 2, true>(a, grid, threads, lds, s) : launch_one<T, V, 8, 2, false>(a, grid, threads, lds, s);
     }
     return (int)hipErrorInvalidValue;
 }

@@ -527,6 +527,11 @@ int build_plan(const Csr& csr, int C, int R, int S, int elem_bytes, const Geomet
     const int SW = p.KW + 1;  // descriptor: first entry, then batches of each of the KW rows
     p.seg.assign(((size_t)p.kblocks * nchunks * p.WK + 1) * SW, 0);   // one terminal descriptor
     p.entries.clear();
+    // Weights that are binary16 values (binary16 layers; cluster-quantised layers, whose centroids are binary16)
+    // go to the device as one word per entry, with the LDS offset in 16 bits: in units of 4 bytes (2 for
+    // 2-byte elements, whose tile must then stay below 128 KB; otherwise the ordinary 8-byte entries are kept).
+    p.off_shift = s.ub >= 4 ? 2 : 1;
+    p.compact = (csr.coded || elem_bytes == 2) && ((long long)p.Cc * p.CS * s.ub >> p.off_shift) < 65536;
     for (int kb = 0; kb < p.kblocks; ++kb)
         for (int ch = 0; ch < nchunks; ++ch) {
             const int c0 = ch * p.Cc, c1 = std::min(C, c0 + p.Cc);
@@ -652,6 +657,15 @@ int check_plan(const Csr& csr, int C, int R, int S, int elem_bytes, const Plan& 
             }
         }
     if ((size_t)p.seg[(size_t)p.kblocks * p.nchunks * p.WK * SW] != pos) return 3;
+    if (p.compact) {   // 8: every entry fits the one-word form (a binary16 weight, an offset of 16 bits in its unit)
+        if (p.off_shift != (ub >= 4 ? 2 : 1)) return 8;
+        for (const Entry& e : p.entries) {
+            float wv;
+            __builtin_memcpy(&wv, &e.wbits, 4);
+            if (half_to_float(float_to_half_rne(wv)) != wv && wv == wv) return 8;
+            if (e.off < 0 || (e.off & ((1 << p.off_shift) - 1)) || (e.off >> p.off_shift) >= 65536) return 8;
+        }
+    }
     if (real != csr.colidx.size()) return 7;                              // 7: every stored weight exactly once
     return 0;
 }

@@ -31,7 +31,8 @@ class LayerRun:
 class Network:
     """Handles of all layers of a workload plus their resident activations."""
 
-    def __init__(self, work: wl.Workload, unify: bool = False, layer_ids: Optional[List[int]] = None):
+    def __init__(self, work: wl.Workload, unify: bool = False, layer_ids: Optional[List[int]] = None,
+                 codebook: bool = False):
         self.work = work
         self.layer_ids = layer_ids
         self.unified = unify
@@ -39,9 +40,14 @@ class Network:
         self.host_weights = []
         for li, spec in enumerate(work.layers, 1):
             lid = layer_ids[li - 1] if layer_ids else li
-            w = wl.make_weights(work.config, lid, spec)
             m = wl.make_mask(work.config, lid, spec)
-            layer = B.SparseConv(w, m, dtype=work.dtype, unify=unify)
+            if codebook:   # cluster-quantised stand-in: 4-bit centroid numbers, 16 binary16 centroids
+                index, centroids = wl.make_codebook(work.config, lid, spec, with_zero=unify)
+                layer = B.SparseConv.from_codebook(index, centroids, m, dtype=work.dtype, unify=unify)
+                w = centroids.astype(np.float16).astype(np.float32)[index]     # the weights the layer stands for
+            else:
+                w = wl.make_weights(work.config, lid, spec)
+                layer = B.SparseConv(w, m, dtype=work.dtype, unify=unify)
             rowptr = layer.csr()[0]
             self.runs.append(LayerRun(spec, layer, int(rowptr[-1])))
             self.host_weights.append((w, m))

@@ -222,9 +222,20 @@ def test_cluster_quantised_weights(dtype, unify):
     xin = oracle.round_through_f16(x) if dtype == "f16" else x
     ref = oracle.sparse_conv((rowptr, colidx, values), xin, spec.K, 3, 3, 1, 1)
     layer = B.SparseConv.from_codebook(index, centroids, mask, dtype=dtype, unify=unify)
-    got = run_gpu(layer, x, 1, 1, dtype)
-    assert_close(got, ref, TOL[dtype], f"codebook-{dtype}-unify{unify}")
+    plain = B.SparseConv(np.zeros(index.shape, np.float32), omask != 0, dtype=dtype)   # same pattern, uncoded
+    for launch in ([0], [0, 0, 0, 0, 4, 0, 0, 0, 0, 0, 2], [0, 1, 2, 2, 3, 0, 1, 0, 0, 5, 1], [4, 2, 1, 4, 5, 0, 2, 0, 2, 1, 1]):
+        layer.set_launch(launch)
+        plain.set_launch(launch)
+        info, pinfo = layer.get_launch(6, spec.H, spec.W, 1, 1), plain.get_launch(6, spec.H, spec.W, 1, 1)
+        # the device reads one word per entry (LDS offset and the centroid as binary16): half the table of the same
+        # pattern as an fp32 layer (binary16 layers have one-word entries whether cluster-quantised or not)
+        assert info["entry_bytes"] == 4 and pinfo["entry_bytes"] == (8 if dtype == "f32" else 4)
+        assert info["entries"] == pinfo["entries"]
+        assert layer.check_plan(6, spec.H, spec.W, 1, 1) == 0
+        got = run_gpu(layer, x, 1, 1, dtype)
+        assert_close(got, ref, TOL[dtype], f"codebook-{dtype}-unify{unify}-{launch}")
     layer.close()
+    plain.close()
 
 
 _OUTPUT_LANE_CASES = [

@@ -37,7 +37,13 @@ def test_static_entry_point_matches_forward_twice_in_a_row(dtype):
     xb = xa[:5, :, :7, :6].copy()                      # smaller batch and map
     split = B.SparseConv(w, m, dtype=dtype)           # its channels dealt over 4 workgroups: partial sums and counters
     split.set_launch([0, 0, 0, 0, 3, 0, 0, 0, 0, 0, 4])   # live in the scratch as well
-    calls = [(layer, w, m, xa, 1, 1), (layer, w, m, xb, 2, 1), (layer, w, m, xa, 1, 1), (other, w2, m2, xc, 1, 0),
+    # a cluster-quantised layer: 4-byte entries and the centroids go through the scratch
+    cen = np.sort(rng.standard_normal(16)).astype(np.float32)
+    index = rng.integers(0, 16, w.shape).astype(np.uint8)
+    coded = B.SparseConv.from_codebook(index, cen, m, dtype=dtype)
+    wc = cen.astype(np.float16).astype(np.float32)[index]
+    calls = [(layer, w, m, xa, 1, 1), (layer, w, m, xb, 2, 1), (coded, wc, m, xa, 1, 1), (layer, w, m, xa, 1, 1),
+             (other, w2, m2, xc, 1, 0), (coded, wc, m, xb, 2, 1),
              (layer, w, m, xb, 2, 1), (split, w, m, xa, 1, 1), (split, w, m, xa, 1, 1), (split, w, m, xb, 2, 1),
              (layer, w, m, xa, 1, 1), (split, w, m, xb, 2, 1)]
     for step, (lay, ww, mm, x, stride, pad) in enumerate(calls):
@@ -59,6 +65,7 @@ def test_static_entry_point_matches_forward_twice_in_a_row(dtype):
     layer.close()
     other.close()
     split.close()
+    coded.close()
 
 
 def test_static_entry_point_rejects_tables_beyond_the_scratch():
