@@ -31,6 +31,7 @@ Plan::~Plan()
     if (d_entries) (void)hipFree(d_entries);
     if (d_seg) (void)hipFree(d_seg);
     if (d_krow) (void)hipFree(d_krow);
+    if (d_units) (void)hipFree(d_units);
     if (d_partial) (void)hipFree(d_partial);
     if (d_counters) (void)hipFree(d_counters);
 }
@@ -153,8 +154,7 @@ void fill_args(const sparse_conv_s* h, const Plan* p, const void* input, void* o
     a.SL = p->SL; a.rows_mode = p->rows_mode; a.tbl_off = p->tbl_off;
     a.SG = p->SG; a.SP = p->SP;
     a.nbuf = p->nbuf;
-    a.npass = (int)(((long long)p->SG * p->Cc * p->SP + (long long)kStage * p->threads - 1) /
-                    ((long long)kStage * p->threads));
+    a.npass = p->npass;
     {
         const long long CP = (long long)p->Cc * p->SP;   // < 2^31: Cc * SP elements fit in LDS
         a.st_dg = (int)(p->threads / CP);
@@ -184,6 +184,9 @@ void fill_args(const sparse_conv_s* h, const Plan* p, const void* input, void* o
     a.fd_EF = make_fastdiv(p->E * p->F);
     a.fd_F = make_fastdiv(p->F);
     a.fd_GW = make_fastdiv((p->G ? p->G : 1) * W);
+    a.units = nullptr;
+    a.nphase = p->nphase > 0 ? p->nphase : 1;
+    a.fd_nphase = make_fastdiv(a.nphase);
 #ifdef SC_PHASE_TIMING
     a.phase = g_phase_buffer;
 #endif
@@ -231,6 +234,7 @@ int forward_impl(sparse_conv_s* h, const void* input, void* output, int N, int H
                     return rc;
                 if ((rc = upload(h, p->seg, &p->d_seg)) != SC_OK) return rc;
                 if ((rc = upload(h, p->krow, &p->d_krow)) != SC_OK) return rc;
+                if (p->G && (rc = upload(h, p->units, &p->d_units)) != SC_OK) return rc;
                 if (p->J > 1) {
                     hipError_t he = hipSuccess;
                     if (!p->d_partial) he = hipMalloc(&p->d_partial, partial_bytes(*p));
@@ -252,6 +256,7 @@ int forward_impl(sparse_conv_s* h, const void* input, void* output, int N, int H
             a.entries = static_cast<const uint32_t*>(p->d_entries);
             a.seg = static_cast<const int*>(p->d_seg);
             a.krow = static_cast<const int*>(p->d_krow);
+            a.units = p->d_units;
             a.partial = static_cast<float*>(p->d_partial);
             a.counters = static_cast<unsigned*>(p->d_counters);
         } else {
@@ -260,7 +265,9 @@ int forward_impl(sparse_conv_s* h, const void* input, void* output, int N, int H
                          b_seg = p->seg.size() * sizeof(int), b_krow = p->krow.size() * sizeof(int);
             const void* entries_at = p->compact ? static_cast<const void*>(p->image4.data()) : static_cast<const void*>(p->image.data());
             const size_t at_seg = round256(b_entries), at_krow = at_seg + round256(b_seg);
-            const size_t at_counters = at_krow + round256(b_krow), at_partial = at_counters + round256(counter_bytes(*p));
+            const size_t b_units = p->units.size() * sizeof(Plan::Unit);
+            const size_t at_units = at_krow + round256(b_krow), at_counters = at_units + round256(b_units),
+                         at_partial = at_counters + round256(counter_bytes(*p));
             if (at_partial + partial_bytes(*p) > kStaticScratchBytes) return SC_ETOOBIG;
             void* base = nullptr;
             int e = static_scratch(&base);
@@ -277,6 +284,7 @@ int forward_impl(sparse_conv_s* h, const void* input, void* output, int N, int H
                 hipError_t he = hipMemcpyAsync(d, entries_at, b_entries, hipMemcpyHostToDevice, s);
                 if (he == hipSuccess) he = hipMemcpyAsync(d + at_seg, p->seg.data(), b_seg, hipMemcpyHostToDevice, s);
                 if (he == hipSuccess) he = hipMemcpyAsync(d + at_krow, p->krow.data(), b_krow, hipMemcpyHostToDevice, s);
+                if (he == hipSuccess && b_units) he = hipMemcpyAsync(d + at_units, p->units.data(), b_units, hipMemcpyHostToDevice, s);
                 // the counters start at zero (every launch leaves them there); whatever the array held before goes
                 if (he == hipSuccess && p->J > 1) he = hipMemsetAsync(d + at_counters, 0, counter_bytes(*p), s);
                 if (he != hipSuccess) {
@@ -288,6 +296,7 @@ int forward_impl(sparse_conv_s* h, const void* input, void* output, int N, int H
             a.entries = reinterpret_cast<const uint32_t*>(d);
             a.seg = reinterpret_cast<const int*>(d + at_seg);
             a.krow = reinterpret_cast<const int*>(d + at_krow);
+            a.units = b_units ? d + at_units : nullptr;
             a.counters = p->J > 1 ? reinterpret_cast<unsigned*>(d + at_counters) : nullptr;
             a.partial = p->J > 1 ? reinterpret_cast<float*>(d + at_partial) : nullptr;
         }

@@ -140,12 +140,23 @@ struct Plan {
     std::vector<int> seg;         // [kblocks][nchunks][WK][1 + KW] = first entry, batches of each row; then one
                                   // terminal descriptor whose first entry is the end of the last segment
     std::vector<int> krow;        // [kblocks][WK][KW] output channel or -1
+    // Output-lane plans: what every thread stages per chunk, worked out here instead of in every workgroup.
+    // Tiles whose first output has the same place within a super-group stage the same pattern; there are
+    // nphase such places (tile t has pattern t % nphase).  units[(ph * npass * kStage + j) * threads + tid] is
+    // the j-th unit of thread tid: .off = source byte offset relative to the tile's first image group at the
+    // chunk's first channel (0x80000000: nothing to load), .dst = byte offset in the first tile buffer.
+    struct Unit {
+        uint32_t off, dst;
+    };
+    int nphase = 0, npass = 0;
+    std::vector<Unit> units;
     std::vector<Batch> image;     // the entry table as the device reads it (built with the first upload)
     unsigned long long id = 0;    // unique per built plan (names what the static device scratch currently holds)
     // device copies (owned)
     void* d_entries = nullptr;
     void* d_seg = nullptr;
     void* d_krow = nullptr;
+    void* d_units = nullptr;
     void* d_partial = nullptr;    // J > 1: partial sums [ntiles * kblocks * J][KW * LP * V][threads] fp32 and ...
     void* d_counters = nullptr;   // ... one arrival counter per (tile, channel block), zero between launches
     bool uploaded = false;
@@ -199,12 +210,14 @@ struct KernelArgs {
     int J, logJ, cpp;        // channel parts per (tile, channel block), its log2, chunks per part
     float* partial;          // J > 1: partial sums of every part, [item][accumulator][thread]
     unsigned* counters;      // J > 1: parts of a (tile, channel block) that have delivered theirs
+    const void* units;       // output lanes: per-thread staging units (Plan::Unit), nphase patterns
+    int nphase;              // output lanes: staging patterns; tile t uses pattern t % nphase
     int real;                // lanes are output elements (else lattice positions)
     int logG;                // log2 of the image groups interleaved per element (0 unless real)
     int PT;                  // real: outputs per tile
     int nout;                // real: outputs of the whole batch = super-groups * E * F
     FastDiv fd_Wp, fd_Hs, fd_W, fd_HW, fd_SP, fd_CP, fd_pitch;  // divisors Wp, Hs, W, H*W, SP, Cc*SP, pitch
-    FastDiv fd_EF, fd_F, fd_GW;                                 // real: divisors E*F, F, G*W
+    FastDiv fd_EF, fd_F, fd_GW, fd_nphase;                      // real: divisors E*F, F, G*W, nphase
 #ifdef SC_PHASE_TIMING
     unsigned long long* phase;  // 8 counters per workgroup, or null
 #endif

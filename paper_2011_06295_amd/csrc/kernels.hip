@@ -139,7 +139,7 @@ struct Vec<T, 1> {
     } while (0)
 #endif
 
-template <typename T, int V, int KW, int LP, bool COMPACT>
+template <typename T, int V, int KW, int LP, bool COMPACT, bool REAL>
 __global__ __launch_bounds__(1024) void tile_kernel(const KernelArgs a)
 {
 #ifdef SC_PHASE_TIMING
@@ -182,7 +182,7 @@ __global__ __launch_bounds__(1024) void tile_kernel(const KernelArgs a)
     // lattice row of its first output; lane l of wavefront wp is image group l % G of output wp * (64 / G) + l / G.
     int Y0, g_first, lrel = 0, lpos, my_o = 0;
     long long q0 = 0;
-    if (a.real) {
+    if constexpr (REAL) {
         const int G1 = (1 << a.logG) - 1;
         const int EF = a.E * a.F;
         const int o0 = tile_id * a.PT;                   // the host guarantees fewer than 2^31 lanes in all
@@ -323,9 +323,12 @@ __global__ __launch_bounds__(1024) void tile_kernel(const KernelArgs a)
     //       of the tile, at channel 0 (0x80000000: the slot is not in the tile)
     //   .y  tile element index at channel 0
     // and staging then only adds channel strides.
+    // (Output lanes: tiles whose first output has the same place in a super-group stage the same pattern, and the
+    // host has worked out every thread's units for each of the few patterns: no table is built here.)
     int2* tbl = reinterpret_cast<int2*>(smem + a.tbl_off);
+    if constexpr (!REAL) {
     for (int sl = tid; sl < a.SL; sl += nthreads) {
-        int gs, ys, xx, Yt, gsub = 0;
+        int gs, ys, xx, Yt;
         if (a.rows_mode == 2) {  // banded tile: element sl is lattice element q0 + band * Wp + offset
             const int band = fdiv(sl, a.fd_pitch);
             const int Ls = (int)q0 + band * a.Wp + (sl - band * a.pitch);
@@ -334,31 +337,28 @@ __global__ __launch_bounds__(1024) void tile_kernel(const KernelArgs a)
             ys = Ys - gs * a.Hs - a.pad;
             xx = Ls - Ys * a.Wp - a.pad;
             Yt = 0;
-        } else if (a.rows_mode) {   // slot = (tile row, image group of the super-group, column)
-            Yt = fdiv(sl, a.fd_GW);
-            const int rem = sl - Yt * (a.W << a.logG);
-            gsub = fdiv(rem, a.fd_W);
-            xx = rem - gsub * a.W;
+        } else if (a.rows_mode) {   // slot = (tile row, column)
+            Yt = fdiv(sl, a.fd_W);
+            xx = sl - Yt * a.W;
             const int Ys = Y0 + Yt;
-            const int us = fdiv(Ys, a.fd_Hs);
-            gs = (us << a.logG) + gsub;
-            ys = Ys - us * a.Hs - a.pad;
+            gs = fdiv(Ys, a.fd_Hs);
+            ys = Ys - gs * a.Hs - a.pad;
         } else {                    // slot = (image group, row, column) of the groups the tile can touch
             const int gi = fdiv(sl, a.fd_HW);
             const int rem = sl - gi * chan_stride;
             ys = fdiv(rem, a.fd_W);
             xx = rem - ys * a.W;
             gs = g_first + gi;
-            gsub = gs & ((1 << a.logG) - 1);
-            Yt = (gs >> a.logG) * a.Hs + a.pad + ys - Y0;
+            Yt = gs * a.Hs + a.pad + ys - Y0;
         }
         const bool ok = gs < a.ngroups && ys >= 0 && ys < a.H && xx >= 0 && xx < a.W && Yt >= 0 && Yt < a.Hb;
         int2 t;
         // (gs - g_first) * V * img_bytes < 2^31 is guaranteed by the host
         t.x = ok ? (int)((unsigned)((gs - g_first) * V) * img_bytes + (unsigned)(ys * a.W + xx) * (unsigned)sizeof(T))
                  : (int)0x80000000;
-        t.y = !ok ? 0 : a.rows_mode == 2 ? sl : ((Yt * a.Wp + a.pad + xx) << a.logG) + gsub;
+        t.y = !ok ? 0 : a.rows_mode == 2 ? sl : Yt * a.Wp + a.pad + xx;
         tbl[sl] = t;
+    }
     }
     // A chunk is SG * Cc * SP units, unit u = (slot group * Cc + channel) * SP + slot: in that
     // order consecutive units are consecutive in memory across the channels of an image.
@@ -389,7 +389,22 @@ __global__ __launch_bounds__(1024) void tile_kernel(const KernelArgs a)
         c -= k2 ? a.Cc : 0;
         gi += a.st_dg + (k2 ? 1 : 0);
     };
+    // output lanes: this thread's units of the tile's pattern, kStage per pass, as the host laid them out
+    const uint2* my_units = nullptr;
+    if constexpr (REAL) {
+        const int phase = tile_id - fdiv(tile_id, a.fd_nphase) * a.nphase;
+        my_units = static_cast<const uint2*>(a.units) + (size_t)phase * a.npass * kStage * nthreads + tid;
+    }
     auto prepare_units = [&]() __attribute__((always_inline)) {
+        if constexpr (REAL) {
+#pragma unroll
+            for (int t = 0; t < kStage; ++t) {
+                const uint2 un = my_units[(size_t)t * nthreads];
+                u_off[t] = un.x;
+                u_dst[t] = tile_at + un.y;
+            }
+            return;
+        }
         gi = fdiv(tid, a.fd_CP);
         const int r0 = tid - gi * a.Cc * a.SP;
         c = fdiv(r0, a.fd_SP);
@@ -418,6 +433,16 @@ __global__ __launch_bounds__(1024) void tile_kernel(const KernelArgs a)
         for (int v = 0; v < V; ++v) VT::set(st_val[t], v, load_elem<T>(f_rs, u_off[t] + (unsigned)v * ib));
     };
     auto fetch_more = [&](int p) __attribute__((always_inline)) {  // pass p >= 1: units decoded on the fly
+        if constexpr (REAL) {
+#pragma unroll
+            for (int t = 0; t < kStage; ++t) {
+                const uint2 un = my_units[(size_t)(p * kStage + t) * nthreads];
+                st_dst[t] = tile_at + un.y;
+#pragma unroll
+                for (int v = 0; v < V; ++v) VT::set(st_val[t], v, load_elem<T>(f_rs, un.x + (unsigned)v * img_bytes));
+            }
+            return;
+        }
         if (p == 1) {  // (gi, c, sp) of unit tid + kStage * nthreads
             gi = fdiv(tid, a.fd_CP);
             const int r0 = tid - gi * a.Cc * a.SP;
@@ -534,7 +559,7 @@ __global__ __launch_bounds__(1024) void tile_kernel(const KernelArgs a)
         }
     };
 
-    __syncthreads();  // slot table complete
+    if constexpr (!REAL) __syncthreads();  // slot table complete
     prepare_units();
     fetch_begin(ch_first);
 #pragma unroll
@@ -632,7 +657,7 @@ __global__ __launch_bounds__(1024) void tile_kernel(const KernelArgs a)
         // lane -> output element (if any) and image group
         int g, oi, oj;
         bool valid;
-        if (a.real) {
+        if constexpr (REAL) {
             const int u = fdiv(my_o, a.fd_EF);
             const int rem = my_o - u * (a.E * a.F);
             oi = fdiv(rem, a.fd_F);
@@ -685,14 +710,14 @@ __global__ __launch_bounds__(1024) void tile_kernel(const KernelArgs a)
 
 namespace {
 
-template <typename T, int V, int KW, int LP, bool COMPACT>
+template <typename T, int V, int KW, int LP, bool COMPACT, bool REAL>
 int launch_one(const KernelArgs& a, int grid, int threads, int lds_bytes, hipStream_t s)
 {
     // accumulators (KW * LP * V floats) plus the reads in flight have to fit a 128-register wavefront
-    if constexpr ((LP > 1 && KW * LP * V > 32) || KW * V > 64) {
+    if constexpr ((LP > 1 && KW * LP * V > 32) || KW * V > 64 || (REAL && LP > 1)) {
         return (int)hipErrorInvalidValue;
     } else {
-    auto fn = tile_kernel<T, V, KW, LP, COMPACT>;
+    auto fn = tile_kernel<T, V, KW, LP, COMPACT, REAL>;
     if (lds_bytes > 64 * 1024) {
         // more than 64 KB of dynamic LDS has to be allowed per kernel and device: once, for the whole 160 KB
         static std::atomic<unsigned long long> allowed{0};   // one bit per device ordinal
@@ -712,19 +737,30 @@ int launch_one(const KernelArgs& a, int grid, int threads, int lds_bytes, hipStr
     }
 }
 
+// one-word entries or not, lanes as outputs or as lattice positions
+template <typename T, int V, int KW, int LP>
+int pick(const KernelArgs& a, int grid, int threads, int lds, hipStream_t s)
+{
+    if (a.real)
+        return a.compact ? launch_one<T, V, KW, LP, true, true>(a, grid, threads, lds, s)
+                         : launch_one<T, V, KW, LP, false, true>(a, grid, threads, lds, s);
+    return a.compact ? launch_one<T, V, KW, LP, true, false>(a, grid, threads, lds, s)
+                     : launch_one<T, V, KW, LP, false, false>(a, grid, threads, lds, s);
+}
+
 template <typename T, int V>
 int launch_kw(int KW, int LP, const KernelArgs& a, int grid, int threads, int lds, hipStream_t s)
 {
     switch (KW * 8 + LP) {
-        case 1 * 8 + 1: return a.compact ? launch_one<T, V, 1, 1, true>(a, grid, threads, lds, s) : launch_one<T, V, 1, 1, false>(a, grid, threads, lds, s);
-        case 2 * 8 + 1: return a.compact ? launch_one<T, V, 2, 1, true>(a, grid, threads, lds, s) : launch_one<T, V, 2, 1, false>(a, grid, threads, lds, s);
-        case 4 * 8 + 1: return a.compact ? launch_one<T, V, 4, 1, true>(a, grid, threads, lds, s) : launch_one<T, V, 4, 1, false>(a, grid, threads, lds, s);
-        case 8 * 8 + 1: return a.compact ? launch_one<T, V, 8, 1, true>(a, grid, threads, lds, s) : launch_one<T, V, 8, 1, false>(a, grid, threads, lds, s);
-        case 16 * 8 + 1: return a.compact ? launch_one<T, V, 16, 1, true>(a, grid, threads, lds, s) : launch_one<T, V, 16, 1, false>(a, grid, threads, lds, s);
-        case 1 * 8 + 2: return a.compact ? launch_one<T, V, 1, 2, true>(a, grid, threads, lds, s) : launch_one<T, V, 1, 2, false>(a, grid, threads, lds, s);
-        case 2 * 8 + 2: return a.compact ? launch_one<T, V, 2, 2, true>(a, grid, threads, lds, s) : launch_one<T, V, 2, 2, false>(a, grid, threads, lds, s);
-        case 4 * 8 + 2: return a.compact ? launch_one<T, V, 4, 2, true>(a, grid, threads, lds, s) : launch_one<T, V, 4, 2, false>(a, grid, threads, lds, s);
-        case 8 * 8 + 2: return a.compact ? launch_one<T, V, 8, 2, true>(a, grid, threads, lds, s) : launch_one<T, V, 8, 2, false>(a, grid, threads, lds, s);
+        case 1 * 8 + 1: return pick<T, V, 1, 1>(a, grid, threads, lds, s);
+        case 2 * 8 + 1: return pick<T, V, 2, 1>(a, grid, threads, lds, s);
+        case 4 * 8 + 1: return pick<T, V, 4, 1>(a, grid, threads, lds, s);
+        case 8 * 8 + 1: return pick<T, V, 8, 1>(a, grid, threads, lds, s);
+        case 16 * 8 + 1: return pick<T, V, 16, 1>(a, grid, threads, lds, s);
+        case 1 * 8 + 2: return pick<T, V, 1, 2>(a, grid, threads, lds, s);
+        case 2 * 8 + 2: return pick<T, V, 2, 2>(a, grid, threads, lds, s);
+        case 4 * 8 + 2: return pick<T, V, 4, 2>(a, grid, threads, lds, s);
+        case 8 * 8 + 2: return pick<T, V, 8, 2>(a, grid, threads, lds, s);
     }
     return (int)hipErrorInvalidValue;
 }

@@ -568,6 +568,63 @@ int build_plan(const Csr& csr, int C, int R, int S, int elem_bytes, const Geomet
         }
     p.seg[(size_t)p.kblocks * nchunks * p.WK * SW] = (int)p.entries.size();  // where the last segment ends
     for (int t = 0; t < kBatch; ++t) p.entries.push_back(Entry{0u, 0});  // slack for look-ahead fetches
+
+    // ---- output lanes: the staging units of every thread, per pattern
+    p.units.clear();
+    p.nphase = 0;
+    p.npass = (int)(((long long)p.SG * p.Cc * p.SP + (long long)kStage * p.threads - 1) / ((long long)kStage * p.threads));
+    if (p.G) {
+        const int EF = p.E * p.F, G = p.G, W = g.W, H = g.H;
+        int a = p.PT % EF, b = EF;
+        while (a) { const int r = b % a; b = a; a = r; }   // b = gcd(PT, EF)
+        p.nphase = EF / b;
+        const long long per_phase = (long long)p.npass * kStage * p.threads;
+        if (per_phase * p.nphase * (long long)sizeof(Plan::Unit) > (8ll << 20)) return SC_EUNSUPPORTED;
+        p.units.resize((size_t)(per_phase * p.nphase));
+        const long long img_bytes = (long long)C * H * W * elem_bytes, chan_bytes = (long long)H * W * elem_bytes;
+        const long long reject = (long long)p.Cc * p.CS;   // the spare element of a buffer
+        for (int ph = 0; ph < p.nphase; ++ph) {
+            const long long o0 = (long long)ph * p.PT;
+            const long long u0 = o0 / EF;
+            const long long Y0 = u0 * p.Hs + (o0 % EF) / p.F * st;
+            const long long g_first = u0 * G;
+            for (long long u = 0; u < per_phase; ++u) {
+                const long long tid = u % p.threads, j = u / p.threads, unit = j * p.threads + tid;
+                const long long gi = unit / ((long long)p.Cc * p.SP), r0 = unit % ((long long)p.Cc * p.SP);
+                const long long c = r0 / p.SP, sp = r0 % p.SP;
+                bool ok = gi < p.SG;
+                long long src = 0, elem = 0;
+                if (ok) {
+                    const long long sl = gi * p.SP + sp;
+                    long long gs, ys, xx, Yt, gsub;
+                    if (p.rows_mode) {   // slot = (tile row, image group of the super-group, column)
+                        Yt = sl / ((long long)G * W);
+                        const long long rem = sl % ((long long)G * W);
+                        gsub = rem / W;
+                        xx = rem % W;
+                        const long long Ys = Y0 + Yt, us = Ys / p.Hs;
+                        gs = us * G + gsub;
+                        ys = Ys - us * p.Hs - pad;
+                    } else {             // slot = (image group, row, column) of the groups the tile can touch
+                        const long long gq = sl / ((long long)H * W), rem = sl % ((long long)H * W);
+                        ys = rem / W;
+                        xx = rem % W;
+                        gs = g_first + gq;
+                        gsub = gs % G;
+                        Yt = gs / G * p.Hs + pad + ys - Y0;
+                    }
+                    // (image groups past the batch are not excluded here: the loads of absent images read zeros)
+                    ok = ys >= 0 && ys < H && xx >= 0 && xx < W && Yt >= 0 && Yt < p.Hb;
+                    src = (gs - g_first) * p.V * img_bytes + (ys * W + xx) * elem_bytes + c * chan_bytes;
+                    elem = (Yt * p.Wp + pad + xx) * G + gsub + c * p.CS;
+                    if (ok && (src < 0 || src >= (1ll << 31))) return SC_EUNSUPPORTED;
+                }
+                Plan::Unit& out = p.units[(size_t)(((long long)ph * p.npass * kStage + j) * p.threads + tid)];
+                out.off = ok ? (uint32_t)src : 0x80000000u;
+                out.dst = (uint32_t)((ok ? elem : reject) * s.ub);
+            }
+        }
+    }
     return SC_OK;
 }
 
@@ -657,6 +714,19 @@ int check_plan(const Csr& csr, int C, int R, int S, int elem_bytes, const Plan& 
             }
         }
     if ((size_t)p.seg[(size_t)p.kblocks * p.nchunks * p.WK * SW] != pos) return 3;
+    if (p.G) {   // 9: the staging units of the output-lane patterns stay inside a tile buffer
+        if (p.nphase < 1 || p.units.size() != (size_t)p.nphase * p.npass * kStage * p.threads) return 9;
+        std::vector<char> hit;
+        for (int ph = 0; ph < p.nphase; ++ph) {
+            hit.assign((size_t)p.Cc * p.CS + 1, 0);
+            for (size_t i = 0; i < (size_t)p.npass * kStage * p.threads; ++i) {
+                const Plan::Unit& un = p.units[(size_t)ph * p.npass * kStage * p.threads + i];
+                if (un.dst % ub != 0 || un.dst / ub > (unsigned long long)p.Cc * p.CS) return 9;
+                if ((un.off & 0x80000000u) && un.dst / ub != (unsigned long long)p.Cc * p.CS) return 9;   // nothing to load: the spare element
+                if (!(un.off & 0x80000000u) && hit[un.dst / ub]++) return 9;                               // one writer per tile element
+            }
+        }
+    }
     if (p.compact) {   // 8: every entry fits the one-word form (a binary16 weight, an offset of 16 bits in its unit)
         if (p.off_shift != (ub >= 4 ? 2 : 1)) return 8;
         for (const Entry& e : p.entries) {

@@ -253,11 +253,20 @@ _OUTPUT_LANE_CASES = [
 def test_lanes_as_outputs(G, dtype):
     """Lanes that stand for output elements only (G image groups interleaved per LDS element) against
     the oracle, every element, for every G, automatic and pinned workgroup shapes."""
+    from paper_2011_06295_amd import binding as B
     rng = np.random.default_rng(500 + G)
+    ran = 0
     for ci, (N, C, K, R, S, H, W, st, p) in enumerate(_OUTPUT_LANE_CASES):
         w, m, x = rand_layer(rng, N, C, K, R, S, H, W, density=0.3)
         for launch in ([0, 0, 0, 0, 0, 0, 0, 0, 0, 1 + G], [0, 2, 3, 2, 5, 0, 1, 0, 2, 1 + G], [0, 4, 1, 4, 0, 0, 1, 0, 0, 1 + G]):
-            check(w, m, x, st, p, dtype, launch=launch, what=f"outputs-G{G}-{dtype}-case{ci}-{launch}")
+            try:
+                check(w, m, x, st, p, dtype, launch=launch, what=f"outputs-G{G}-{dtype}-case{ci}-{launch}")
+                ran += 1
+            except B.SparseConvError as e:
+                # a pinned G whose tiles start at too many different places of a super-group (a 43-wide
+                # map in tiles of 8 outputs: 301 staging patterns) is refused, never planned unasked
+                assert e.code == B.SC_EUNSUPPORTED and (H, W) == (5, 40), (ci, launch, e)
+    assert ran >= 27
 
 
 @pytest.mark.parametrize("dtype", ["f32", "f16"])
