@@ -145,7 +145,7 @@ def main():
                     help="measure the roofs instead of a workload: LDS read rate of the gather's access pattern and the "
                          "rate of a plain copy, with the library's probe kernels; prints one JSON line")
     ap.add_argument("--launch", default="", help="comma separated launch override applied to every layer")
-    ap.add_argument("--autotune", type=int, default=8,
+    ap.add_argument("--autotune", type=int, default=12,
                     help="before the warm-up, let every layer measure this many of its best-ranked launch "
                          "configurations and keep the fastest (0: the cost estimate's first choice)")
     ap.add_argument("--compare-dense", action="store_true",

@@ -45,6 +45,11 @@ __device__ __forceinline__ const SC_CONSTANT T* as_constant(const T* p)
 {
     return (const SC_CONSTANT T*)(p);
 }
+// The kernel's argument block as it lies in the kernel-argument segment (the one by-value argument starts it).
+__device__ __forceinline__ const SC_CONSTANT KernelArgs* argument_segment()
+{
+    return (const SC_CONSTANT KernelArgs*)(__builtin_amdgcn_kernarg_segment_ptr());
+}
 #pragma clang diagnostic pop
 
 // LDS addressed by its 32-bit address: what a read takes is the sum the kernel formed, as it is
@@ -69,7 +74,8 @@ __device__ __forceinline__ void lds_write(unsigned address, const Vt& value)
 #pragma clang diagnostic pop
 
 // n / d for 0 <= n < 2^31 with the multiplier prepared on the host.
-__device__ __forceinline__ int fdiv(int n, const FastDiv& f)
+template <typename FD>   // a FastDiv in whatever address space
+__device__ __forceinline__ int fdiv(int n, const FD& f)
 {
     return f.d == 1 ? n : (int)(__umulhi((unsigned)n, f.mul) >> f.shift);
 }
@@ -602,6 +608,14 @@ __global__ __launch_bounds__(1024) void tile_kernel(const KernelArgs a)
         }
     }
 
+    // What follows needs launch constants that nothing before it uses (output pointer, channel slots, bias, the
+    // exchange buffers of split channels, the divisors of the store's position decode).  Held in scalar registers
+    // from the kernel's start they would be spilled across the whole multiply loop; they are read here instead,
+    // from the kernel-argument segment, through a pointer the compiler cannot trace back to it.
+    const SC_CONSTANT KernelArgs* late = argument_segment();
+    asm volatile("" : "+s"(late));
+    const SC_CONSTANT KernelArgs& la = *late;
+
     // ---- channel parts: every part leaves its sums in global memory; the one that finds all others done
     // (a counter per (tile, channel block), back at zero when the launch ends) adds them up in the order of
     // the parts, whichever came last, and goes on to the store.  The sums travel as device-scope atomic
@@ -609,9 +623,9 @@ __global__ __launch_bounds__(1024) void tile_kernel(const KernelArgs a)
     // device-scope atomic: no cache of the chip is flushed or invalidated as a whole, which a device-scope
     // fence would do (measured: it made a 27 us layer take 78).  A part's stores are complete (the wait at
     // the workgroup-scope fence) before its arrival is counted.
-    if (a.J > 1) {
+    if (la.J > 1) {
         constexpr int kAcc = KW * LP * V;
-        float* mine = a.partial + (size_t)item * kAcc * nthreads + tid;
+        float* mine = la.partial + (size_t)item * kAcc * nthreads + tid;
 #pragma unroll
         for (int kk = 0; kk < KW; ++kk)
 #pragma unroll
@@ -623,18 +637,18 @@ __global__ __launch_bounds__(1024) void tile_kernel(const KernelArgs a)
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // this wavefront's stores have completed
         __syncthreads();                                         // ... and every wavefront's; nobody reads the tile any more
         unsigned* ticket = reinterpret_cast<unsigned*>(smem);
-        if (tid == 0) *ticket = __hip_atomic_fetch_add(a.counters + pair, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (tid == 0) *ticket = __hip_atomic_fetch_add(la.counters + pair, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         __syncthreads();
-        if (*ticket != (unsigned)(a.J - 1)) return;
-        if (tid == 0) __hip_atomic_store(a.counters + pair, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        const float* all = a.partial + (size_t)(pair << a.logJ) * kAcc * nthreads + tid;
+        if (*ticket != (unsigned)(la.J - 1)) return;
+        if (tid == 0) __hip_atomic_store(la.counters + pair, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const float* all = la.partial + (size_t)(pair << la.logJ) * kAcc * nthreads + tid;
 #pragma unroll
         for (int kk = 0; kk < KW; ++kk)
 #pragma unroll
             for (int p = 0; p < LP; ++p)
 #pragma unroll
                 for (int v = 0; v < V; ++v) acc[kk][p][v] = 0.f;
-        for (int j = 0; j < a.J; ++j) {   // in the order of the parts; all loads of a part are in flight together
+        for (int j = 0; j < la.J; ++j) {   // in the order of the parts; all loads of a part are in flight together
             float got[kAcc];
 #pragma unroll
             for (int i = 0; i < kAcc; ++i)
@@ -649,47 +663,47 @@ __global__ __launch_bounds__(1024) void tile_kernel(const KernelArgs a)
     }
 
     // ---- store: one writer per output element
-    T* __restrict__ y = static_cast<T*>(a.y);
-    const SC_CONSTANT int* kr = as_constant(a.krow) + ((size_t)kb * a.WK + wk) * KW;
-    const size_t plane = (size_t)a.E * a.F;
+    T* __restrict__ y = static_cast<T*>(la.y);
+    const SC_CONSTANT int* kr = as_constant(la.krow) + ((size_t)kb * la.WK + wk) * KW;
+    const size_t plane = (size_t)la.E * la.F;
 #pragma unroll
     for (int p = 0; p < LP; ++p) {
         // lane -> output element (if any) and image group
         int g, oi, oj;
         bool valid;
         if constexpr (REAL) {
-            const int u = fdiv(my_o, a.fd_EF);
-            const int rem = my_o - u * (a.E * a.F);
-            oi = fdiv(rem, a.fd_F);
-            oj = rem - oi * a.F;
-            g = (u << a.logG) + (lane & ((1 << a.logG) - 1));
-            valid = my_o < a.nout && g < a.ngroups;
+            const int u = fdiv(my_o, la.fd_EF);
+            const int rem = my_o - u * (la.E * la.F);
+            oi = fdiv(rem, la.fd_F);
+            oj = rem - oi * la.F;
+            g = (u << la.logG) + (lane & ((1 << la.logG) - 1));
+            valid = my_o < la.nout && g < la.ngroups;
         } else {
             const int rel = lrel + p * 64;
-            const int Yl = fdiv(rel, a.fd_Wp);
-            const int X = rel - Yl * a.Wp;
+            const int Yl = fdiv(rel, la.fd_Wp);
+            const int X = rel - Yl * la.Wp;
             const int Y = Y0 + Yl;
-            g = fdiv(Y, a.fd_Hs);
-            const int yy = Y - g * a.Hs;
-            oi = yy / a.stride;
-            oj = X / a.stride;
-            valid = g < a.ngroups && oi * a.stride == yy && oj * a.stride == X && oi < a.E && oj < a.F;
+            g = fdiv(Y, la.fd_Hs);
+            const int yy = Y - g * la.Hs;
+            oi = yy / la.stride;
+            oj = X / la.stride;
+            valid = g < la.ngroups && oi * la.stride == yy && oj * la.stride == X && oi < la.E && oj < la.F;
         }
         if (!valid) continue;
-        const size_t pix = (size_t)oi * a.F + oj;
+        const size_t pix = (size_t)oi * la.F + oj;
 #pragma unroll
         for (int kk = 0; kk < KW; ++kk) {
             const int k = kr[kk];
             if (k < 0) continue;
-            const float bias = a.bias ? as_constant(a.bias)[k] : 0.f;  // section 3: bias, then activation
+            const float bias = la.bias ? as_constant(la.bias)[k] : 0.f;  // section 3: bias, then activation
 #pragma unroll
             for (int v = 0; v < V; ++v) {
                 const int n = g * V + v;
                 float r = acc[kk][p][v] + bias;
-                if (a.relu) r = r > 0.f ? r : 0.f;
-                if (n >= a.N) continue;
-                T* at = &y[((size_t)n * a.K + k) * plane + pix];
-                if (a.nt_store)
+                if (la.relu) r = r > 0.f ? r : 0.f;
+                if (n >= la.N) continue;
+                T* at = &y[((size_t)n * la.K + k) * plane + pix];
+                if (la.nt_store)
                     store_nontemporal(at, (T)r);
                 else
                     *at = (T)r;

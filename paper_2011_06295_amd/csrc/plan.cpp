@@ -355,6 +355,13 @@ int build_plan(const Csr& csr, int C, int R, int S, int elem_bytes, const Geomet
                         // tile buffer(s), each with one spare element, table
                         const long long lds = ((long long)nbuf * ((long long)Cc * CS + 1) * s.ub + 15) / 16 * 16 + tbl;
                         if (lds > kMaxLds) continue;
+                        if (G) {   // the staging patterns of output-lane tiles must stay a small table (build below)
+                            int ga = (span / G) % EF, gb = EF;
+                            while (ga) { const int r = gb % ga; gb = ga; ga = r; }
+                            const long long per = (SL * Cc + (long long)kStage * kWave * wp * wk - 1) / ((long long)kStage * kWave * wp * wk) *
+                                                  ((long long)kStage * kWave * wp * wk);
+                            if (per * (EF / gb) * 8 > (8ll << 20)) continue;
+                        }
                         // More channel blocks than the rows need leave slots empty, which relieves the
                         // last wavefronts of the fullest SIMDs (rows_per_wavefront): up to two extra.
                         const int kb_min = cdiv(K, wk * kw);
@@ -409,12 +416,16 @@ int build_plan(const Csr& csr, int C, int R, int S, int elem_bytes, const Geomet
             if (!seen) uniq.push_back(e);
             if (uniq.size() >= 256) break;
         }
-        // The estimate was fitted on lattice lanes and ranks the kinds of lanes against each other only roughly: the
-        // list goes round the kinds (best of each, second best of each, ...) so that a measurement of the first few
-        // sees every kind.
+        // The estimate was fitted on lattice lanes and ranks the kinds of lanes (and of channel splitting) against
+        // each other only roughly: after its three best, the list goes round the kinds (best of each, second best
+        // of each, ...) so that a measurement of the first few sees every kind.
         {
             std::vector<std::pair<double, Launch>> mixed;
             std::vector<char> used(uniq.size(), 0);
+            for (size_t i = 0; i < uniq.size() && i < 3; ++i) {
+                used[i] = 1;
+                mixed.push_back(uniq[i]);
+            }
             while (mixed.size() < uniq.size() && mixed.size() < 64) {
                 bool took[36] = {};
                 for (size_t i = 0; i < uniq.size() && mixed.size() < 64; ++i) {

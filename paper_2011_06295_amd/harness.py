@@ -164,7 +164,11 @@ class Network:
             return (self.work.N, run.spec.H, run.spec.W, run.spec.stride, run.spec.pad)
 
         def time_layer(li, launch):
-            self.runs[li].layer.set_launch(launch)
+            try:
+                self.runs[li].layer.set_launch(launch)
+                self.runs[li].layer.get_launch(*geom(self.runs[li]))
+            except B.SparseConvError:
+                return float("inf")          # a candidate this geometry cannot run
             t = 0.0
             for j in range(2 + steps):
                 sets = getattr(self, "sets", None)

@@ -292,7 +292,7 @@ def test_launch_choice_rechecked_inside_a_pass_keeps_the_results():
 
 def _tune_as_bench_does(net):
     """The launch selection of bench.py's default run, step by step."""
-    net.autotune(8)
+    net.autotune(12)
     net.make_buffer_sets(512 << 20)
     return net.refine_in_context(top=4)
 
