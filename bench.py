@@ -154,7 +154,7 @@ def main():
     ap.add_argument("--buffer-mib", type=int, default=512,
                     help="the timed steps go round copies of the resident activations that together hold at least "
                          "this much (at most 16 copies), so that the last-level cache cannot serve them; 0: one set")
-    ap.add_argument("--refine-top", type=int, default=4,
+    ap.add_argument("--refine-top", type=int, default=12,
                     help="best-ranked candidates the second look times beside the measured choice")
     ap.add_argument("--unify", action="store_true",
                     help="create the layers with the unify flag (rows padded with explicit zeros to the fullest row's "

@@ -155,22 +155,23 @@ class Network:
         """Second look at every layer's launch choice, inside a pass: sparse_conv_autotune times a
         layer repeated on the same buffers (which stay in the last-level cache if they fit), and
         that flatters some configurations.  Per layer the measured choice and the `top` candidates
-        the cost estimate ranks best are run in pass order (going round the buffer sets if there
-        are any) with events around that layer only; the two fastest are run once more with the
-        other kind of output store, and the fastest of all is pinned."""
+        the planner ranks first are run in pass order (going round the buffer sets if there are
+        any) with events around that layer only, briefly; the three fastest are then timed for
+        `steps` passes each, the two fastest of those once more with the other kind of output
+        store, and the fastest of all is pinned."""
         import torch
 
         def geom(run):
             return (self.work.N, run.spec.H, run.spec.W, run.spec.stride, run.spec.pad)
 
-        def time_layer(li, launch):
+        def time_layer(li, launch, passes):
             try:
                 self.runs[li].layer.set_launch(launch)
                 self.runs[li].layer.get_launch(*geom(self.runs[li]))
             except B.SparseConvError:
                 return float("inf")          # a candidate this geometry cannot run
             t = 0.0
-            for j in range(2 + steps):
+            for j in range(2 + passes):
                 sets = getattr(self, "sets", None)
                 bufs = sets[j % len(sets)] if sets else [(r.x, r.y) for r in self.runs]
                 e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -183,7 +184,7 @@ class Network:
                 torch.cuda.synchronize()
                 if j >= 2:
                     t += e0.elapsed_time(e1)
-            return t
+            return t / passes
 
         for li, run in enumerate(self.runs):
             d = run.layer.get_launch(*geom(run))
@@ -193,11 +194,14 @@ class Network:
             for c in run.layer.rank_launches(*geom(run), max_candidates=top):
                 if c[:8] + c[9:] not in [k[:8] + k[9:] for k in cands]:
                     cands.append(c)
-            timed = sorted((time_layer(li, c), c) for c in cands)
-            for t, c in list(timed[:2]):
+            if len(cands) > 3:
+                brief = sorted((time_layer(li, c, max(2, steps // 3)), i) for i, c in enumerate(cands))
+                cands = [cands[i] for _, i in brief[:3]]
+            timed = sorted(((time_layer(li, c, steps), i, c) for i, c in enumerate(cands)), key=lambda e: e[:2])
+            for t, i, c in list(timed[:2]):
                 other = c[:8] + [3 - c[8]] + c[9:]
-                timed.append((time_layer(li, other), other))
-            run.layer.set_launch(min(timed)[1])
+                timed.append((time_layer(li, other, steps), len(timed), other))
+            run.layer.set_launch(min(timed, key=lambda e: e[:2])[2])
         return [run.layer.get_launch(*geom(run)) for run in self.runs]
 
     def make_buffer_sets(self, min_bytes: int = 512 << 20, max_sets: int = 16) -> int:
