@@ -263,6 +263,8 @@ __global__ __launch_bounds__(1024) void tile_kernel(const KernelArgs a)
     const SC_CONSTANT uint32_t* e = nullptr;   // epd * kBatch dwords per batch
     int nb[KW];
     Batch cur;
+    Batch ahead;   // the batch after cur (deep pipeline only)
+    constexpr bool kDeep = REAL && LP == 1 && sizeof(T) == 4;   // whole batches of reads in flight (see compute)
     auto fetch_batch = [&](Batch& b, const SC_CONSTANT uint32_t* p) __attribute__((always_inline)) {
 #pragma unroll
         for (int u = 0; u < kBatch; ++u) b.w[u] = p[u];
@@ -294,7 +296,11 @@ __global__ __launch_bounds__(1024) void tile_kernel(const KernelArgs a)
         e = as_constant(a.entries) + (size_t)epd * (size_t)d_start;
 #pragma unroll
         for (int kk = 0; kk < KW; ++kk) nb[kk] = d_nb[kk];
-        fetch_batch(cur, e);  // the table ends in kBatch slack entries
+        fetch_batch(cur, e);  // the table ends in 2 * kBatch slack entries
+        if constexpr (kDeep) {
+            e += epd * kBatch;
+            fetch_batch(ahead, e);
+        }
         if (ch + 1 < ch_end) {
             sg += sg_step;
             d_start = sg[0];
@@ -495,6 +501,24 @@ __global__ __launch_bounds__(1024) void tile_kernel(const KernelArgs a)
 #pragma unroll
             for (int p = 0; p < LP; ++p) asm volatile("" ::"v"(x[u][p]));
     };
+    // A SIMD issues from the oldest of its ready wavefronts first, so the four wavefronts it holds of a
+    // workgroup would finish a chunk one after the other, and the last of them would run alone, at the
+    // rate at which one wavefront can hide its own read latencies.  The wavefront's issue priority therefore
+    // falls as it gets through its rows: highest while more than half of them are left, then while more
+    // than a quarter, more than an eighth, lowest after that.  Those behind are served first, and all
+    // reach the end of the chunk within the last few rows of each other.
+    auto level = [](int kk) constexpr { const int left = KW - kk; return left * 2 > KW ? 3 : left * 4 > KW ? 2 : left * 8 > KW ? 1 : 0; };
+    auto yield_to_slower = [&](int kk) __attribute__((always_inline)) {
+        if constexpr (KW >= 2) {
+            if (kk > 0 && level(kk) == level(kk - 1)) return;
+            switch (level(kk)) {
+                case 3: __builtin_amdgcn_s_setprio(3); break;
+                case 2: __builtin_amdgcn_s_setprio(2); break;
+                case 1: __builtin_amdgcn_s_setprio(1); break;
+                default: __builtin_amdgcn_s_setprio(0); break;
+            }
+        }
+    };
     auto compute = [&](int base, bool prefetch) __attribute__((always_inline)) {
         vec xs[2][kGroup][LP];
         static_assert(kGroup == 2, "a group is the two entries whose offsets share a 64-bit scalar");
@@ -520,6 +544,99 @@ __global__ __launch_bounds__(1024) void tile_kernel(const KernelArgs a)
                     for (int v = 0; v < V; ++v) ac[p][v] = __builtin_fmaf(w, (float)VT::get(x[u][p], v), ac[p][v]);
             }
         };
+        if constexpr (kDeep) {
+            // One position per lane: a whole batch of reads is in flight while the multiply-adds of the
+            // batch before it run (twice the distance between a read and its use that the grouped form
+            // below has).  Three batches are live: `cur` (its reads issued), `ahead` (requested a step
+            // ago) and the one a step requests.  The two read buffers p and q (eight separate registers-to-be,
+            // not an array: an array of them is handled as one wide value and moved about as a whole where
+            // control flow joins) take turns; a row with an odd number of batches ends in a step that reads the
+            // next batch into the registers it has just used, one by one, so that every row begins in p.
+            static_assert(kBatch == 4, "the read buffers below are written out for four entries");
+            vec p0, p1, p2, p3, q0, q1, q2, q3;
+            auto fma1 = [&](const vec& x, uint32_t word, float (&ac)[LP][V]) __attribute__((always_inline)) {
+                const float w = weight(word);
+#pragma unroll
+                for (int v = 0; v < V; ++v) ac[0][v] = __builtin_fmaf(w, (float)VT::get(x, v), ac[0][v]);
+            };
+            auto arrived4 = [](const vec& x0, const vec& x1, const vec& x2, const vec& x3) __attribute__((always_inline)) {
+                asm volatile("" ::"v"(x0));
+                asm volatile("" ::"v"(x1));
+                asm volatile("" ::"v"(x2));
+                asm volatile("" ::"v"(x3));
+            };
+            {
+                decode(cur);
+                const unsigned long long lo = base2 + cur.off2[0], hi = base2 + cur.off2[1];
+                p0 = lds_read<vec>((unsigned)lo);
+                p1 = lds_read<vec>((unsigned)(lo >> 32));
+                p2 = lds_read<vec>((unsigned)hi);
+                p3 = lds_read<vec>((unsigned)(hi >> 32));
+            }
+            // a step: the reads of A (into x) and the fetch of B have been issued before; wait for both, issue
+            // B's reads into y and the fetch of the batch after B into C, then run A's multiply-adds
+            auto step = [&](const Batch& A, Batch& B, Batch& C, vec& x0, vec& x1, vec& x2, vec& x3, vec& y0, vec& y1, vec& y2,
+                            vec& y3, float (&ac)[LP][V]) __attribute__((always_inline)) {
+                __builtin_amdgcn_sched_barrier(0);
+                arrived4(x0, x1, x2, x3);
+                decode(B);
+                const unsigned long long lo = base2 + B.off2[0], hi = base2 + B.off2[1];
+                y0 = lds_read<vec>((unsigned)lo);
+                y1 = lds_read<vec>((unsigned)(lo >> 32));
+                y2 = lds_read<vec>((unsigned)hi);
+                y3 = lds_read<vec>((unsigned)(hi >> 32));
+                e += epd * kBatch;
+                fetch_batch(C, e);
+                __builtin_amdgcn_sched_barrier(0);
+                fma1(x0, A.w[0], ac);
+                fma1(x1, A.w[1], ac);
+                fma1(x2, A.w[2], ac);
+                fma1(x3, A.w[3], ac);
+                __builtin_amdgcn_sched_barrier(0);
+            };
+#pragma unroll
+            for (int kk = 0; kk < KW; ++kk) {
+                yield_to_slower(kk);
+                if (prefetch) {
+#pragma unroll
+                    for (int t = kk * kStage / KW; t < (kk + 1) * kStage / KW; ++t) fetch_unit(t);
+                }
+                int b = 0;
+                for (; b + 2 <= nb[kk]; b += 2) {
+                    Batch far, farther;
+                    step(cur, ahead, far, p0, p1, p2, p3, q0, q1, q2, q3, acc[kk]);
+                    step(ahead, far, farther, q0, q1, q2, q3, p0, p1, p2, p3, acc[kk]);
+                    cur = far;
+                    ahead = farther;
+                }
+                if (b < nb[kk]) {
+                    Batch far;
+                    __builtin_amdgcn_sched_barrier(0);
+                    arrived4(p0, p1, p2, p3);
+                    decode(ahead);
+                    const unsigned long long lo = base2 + ahead.off2[0], hi = base2 + ahead.off2[1];
+                    e += epd * kBatch;
+                    fetch_batch(far, e);
+                    __builtin_amdgcn_sched_barrier(0);
+                    fma1(p0, cur.w[0], acc[kk]);
+                    p0 = lds_read<vec>((unsigned)lo);
+                    __builtin_amdgcn_sched_barrier(0);
+                    fma1(p1, cur.w[1], acc[kk]);
+                    p1 = lds_read<vec>((unsigned)(lo >> 32));
+                    __builtin_amdgcn_sched_barrier(0);
+                    fma1(p2, cur.w[2], acc[kk]);
+                    p2 = lds_read<vec>((unsigned)hi);
+                    __builtin_amdgcn_sched_barrier(0);
+                    fma1(p3, cur.w[3], acc[kk]);
+                    p3 = lds_read<vec>((unsigned)(hi >> 32));
+                    __builtin_amdgcn_sched_barrier(0);
+                    cur = ahead;
+                    ahead = far;
+                }
+            }
+            arrived4(p0, p1, p2, p3);   // the reads issued for the batch after the last one end here
+            return;
+        }
         decode(cur);
         gather(xs[0], cur, 0);
         arrived(xs[0]);
@@ -548,6 +665,7 @@ __global__ __launch_bounds__(1024) void tile_kernel(const KernelArgs a)
         };
 #pragma unroll
         for (int kk = 0; kk < KW; ++kk) {
+            yield_to_slower(kk);
             if (prefetch) {  // this row's share of the next chunk's staging loads
 #pragma unroll
                 for (int t = kk * kStage / KW; t < (kk + 1) * kStage / KW; ++t) fetch_unit(t);
@@ -594,6 +712,7 @@ __global__ __launch_bounds__(1024) void tile_kernel(const KernelArgs a)
         }
         SC_PHASE(1);
         compute(((ch - ch_first) & (a.nbuf - 1)) * tile_bytes + lposb, more);  // chunk ch+1's loads are issued along the way
+        if constexpr (KW >= 2) __builtin_amdgcn_s_setprio(3);   // what follows is short and others wait for it
         SC_PHASE(2);
         if (more) {
             begin_chunk(ch + 1);

@@ -578,7 +578,7 @@ int build_plan(const Csr& csr, int C, int R, int S, int elem_bytes, const Geomet
             }
         }
     p.seg[(size_t)p.kblocks * nchunks * p.WK * SW] = (int)p.entries.size();  // where the last segment ends
-    for (int t = 0; t < kBatch; ++t) p.entries.push_back(Entry{0u, 0});  // slack for look-ahead fetches
+    for (int t = 0; t < 2 * kBatch; ++t) p.entries.push_back(Entry{0u, 0});  // slack for look-ahead fetches (two batches)
 
     // ---- output lanes: the staging units of every thread, per pattern
     p.units.clear();
