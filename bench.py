@@ -162,6 +162,8 @@ def main():
     ap.add_argument("--refine", type=int, default=1,
                     help="1: after the measured launch choice, time each layer's choice, the cost estimate's first choice "
                          "and both kinds of output store inside a pass and keep the fastest (0: skip)")
+    ap.add_argument("--graph", type=int, default=1,
+                    help="1: also record the K timed steps into one HIP graph and report its replay per step (0: skip)")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="after the timed steps, copy a device buffer of this size once (a kernel of known "
                          "traffic that calibrates rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
@@ -184,6 +186,7 @@ def main():
         for name in CONFIG_LINES:
             r = run_workload(name, args, min(args.steps, 20), min(args.warmup, 5), brief=True)
             line = {"workload": name, "batch": r["config"]["batch"], "dtype": r["dtype"], "ms_per_step": r["ms_per_step"],
+                    "graph_ms_per_step": r["graph_ms_per_step"],
                     "value": r["value"], "unit": r["unit"], "bound": r["roofline"]["bound"],
                     "roofline_frac": r["roofline"]["frac"], "lds_frac": r["roofline"]["lds_frac"],
                     "launches_per_step": r["roofline"]["launches_per_step"]}
@@ -264,15 +267,17 @@ def run_workload(name, args, steps, warmup, brief):
     if tune and args.refine:
         net.refine_in_context(top=args.refine_top)
 
+    runners = net.prepare_steps()   # one per buffer set: the step's calls, checked and marshalled beforehand
+
     def timed(rotate):
         for i in range(warmup):
-            net.step(i if rotate else 0)
+            runners[i % nsets if rotate else 0]()
         torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         t0 = time.perf_counter()
         e0.record()
         for i in range(steps):
-            net.step(i if rotate else 0)
+            runners[i % nsets if rotate else 0]()
         e1.record()
         torch.cuda.synchronize()
         return time.perf_counter() - t0, e0.elapsed_time(e1)
@@ -280,6 +285,31 @@ def run_workload(name, args, steps, warmup, brief):
     hot_wall = timed(False)[0] if not brief else 0.0
     wall, gpu_ms = timed(True)
     ms_per_step = wall * 1e3 / steps
+
+    # The same K steps recorded once into a HIP graph (on a stream of their own) and replayed: what the step
+    # costs when the host issues one graph launch instead of a launch per layer.  The launches record no
+    # memset nodes and allocate nothing once every geometry has run.
+    graph_ms = None
+    if args.graph:
+        side = torch.cuda.Stream()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            recorded = net.prepare_steps()
+            with torch.cuda.graph(graph, stream=side):
+                for i in range(steps):
+                    recorded[i % nsets]()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        best = None
+        for _ in range(3):
+            t0 = time.perf_counter()
+            graph.replay()
+            torch.cuda.synchronize()
+            t = time.perf_counter() - t0
+            best = t if best is None else min(best, t)
+        graph_ms = best * 1e3 / steps
+        del graph
 
     # per-layer durations, in the order and cache state of a step: events between the launches of
     # further (untimed) steps on the launch stream
@@ -355,6 +385,7 @@ def run_workload(name, args, steps, warmup, brief):
         "n_gpus": 1, "steps": steps, "warmup": warmup,
         "ms_per_step": ms_per_step, "gpu_ms_per_step": gpu_ms / steps,
         "cache_hot_ms_per_step": hot_wall * 1e3 / steps, "buffer_sets": nsets,
+        "graph_ms_per_step": graph_ms,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": work.dtype, "data": "synthetic" + (", cluster-quantised weights (4-bit numbers, 16 centroids)" if args.codebook else ""),
         "config": {"workload": f"{work.name}, batch {N}, {nl} sparse conv layer(s), conv only, inputs resident in HBM, {nsets} buffer set(s) in rotation",

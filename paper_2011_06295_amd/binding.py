@@ -289,10 +289,15 @@ class SparseConv:
         if not x.is_cuda or x.dtype != want or not x.is_contiguous() or x.dim() != 4 or x.shape[1] != self.C:
             raise ValueError("input must be a contiguous CUDA tensor [N][C][H][W] of the layer's dtype")
         N, _, H, W = x.shape
-        E, F = self.output_shape(H, W, stride, pad)
+        try:      # the output shape of a geometry is asked of the library once (a forward call is a few microseconds)
+            E, F = self._shapes[(H, W, stride, pad)]
+        except (AttributeError, KeyError):
+            if not hasattr(self, "_shapes"):
+                self._shapes = {}
+            E, F = self._shapes[(H, W, stride, pad)] = self.output_shape(H, W, stride, pad)
         if out is None:
             out = torch.empty((N, self.K, E, F), dtype=want, device=x.device)
-        elif tuple(out.shape) != (N, self.K, E, F) or out.dtype != want or not out.is_contiguous():
+        elif out.shape != (N, self.K, E, F) or out.dtype != want or not out.is_contiguous():
             raise ValueError("bad output tensor")
         return out, (N, H, W, stride, pad), torch.cuda.current_stream(x.device).cuda_stream
 
@@ -306,6 +311,21 @@ class SparseConv:
         out, geom, stream = self._buffers(x, stride, pad, out)
         sparse_conv_forward(self.handle, x.data_ptr(), out.data_ptr(), *geom, stream)
         return out
+
+    def prepare(self, x, stride: int = 1, pad: int = 0, out=None):
+        """Checks the tensors once and returns a function without arguments that enqueues this convolution of x
+        into out on the stream that is current now (its attribute `out` is the output tensor).  For loops that
+        repeat a call on the same buffers: what is left per call is the library call itself."""
+        out, geom, stream = self._buffers(x, stride, pad, out)
+        fn, h, xp, op, st = _lib.sparse_conv_forward, self.handle, x.data_ptr(), out.data_ptr(), stream or None
+
+        def enqueue(_keep=(x, out)):
+            rc = fn(h, xp, op, *geom, st)
+            if rc:
+                _check(rc, "sparse_conv_forward", h)
+
+        enqueue.out = out
+        return enqueue
 
     def forward_static(self, x, stride: int = 1, pad: int = 0, out=None):
         """forward for callers that cannot allocate device memory (`out` should then be given)."""

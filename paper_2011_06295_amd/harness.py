@@ -134,6 +134,7 @@ class Network:
         """Pushes x0 through every layer once, keeping each layer's input and output on the device
         (dispatch: every layer through the implementation its route names)."""
         import torch
+        self._prepared = {}   # calls prepared by step() refer to the buffers replaced here
         x = torch.from_numpy(x0).cuda().to(self.torch_dtype()).contiguous()
         for li, run in enumerate(self.runs, 1):
             if not self.work.chain and li > 1:   # independent layers: each has its own seeded input
@@ -211,11 +212,28 @@ class Network:
         import torch
         per_set = sum(r.x.numel() * r.x.element_size() + r.y.numel() * r.y.element_size() for r in self.runs)
         nsets = max(1, min(max_sets, -(-min_bytes // per_set)))
+        self._prepared = {}
         self.sets = [[(r.x, r.y) for r in self.runs]]
         for _ in range(nsets - 1):
             self.sets.append([(r.x.clone(), torch.empty_like(r.y)) for r in self.runs])
         torch.cuda.synchronize()
         return nsets
+
+    def prepare_steps(self):
+        """One function per buffer set that enqueues a pass of the hot path on that set, on the stream that is
+        current now, with every call checked and marshalled beforehand (step() does the same lookup per call;
+        for launch-bound workloads even that shows)."""
+        sets = getattr(self, "sets", None) or [[(r.x, r.y) for r in self.runs]]
+        runners = []
+        for bufs in sets:
+            calls = tuple(run.layer.prepare(x, run.spec.stride, run.spec.pad, out=y) for run, (x, y) in zip(self.runs, bufs))
+
+            def run_set(calls=calls):
+                for enqueue in calls:
+                    enqueue()
+
+            runners.append(run_set)
+        return runners
 
     def step(self, which: int = 0, dispatch: bool = False):
         """One pass of the hot path: every layer's convolution on its resident input
@@ -224,8 +242,17 @@ class Network:
         sets = getattr(self, "sets", None)
         bufs = sets[which % len(sets)] if sets else [(r.x, r.y) for r in self.runs]
         if not dispatch:
-            for run, (x, y) in zip(self.runs, bufs):
-                run.layer.forward(x, run.spec.stride, run.spec.pad, out=y)
+            import torch
+            # the calls of a buffer set are checked and marshalled once per stream, then only enqueued
+            key = (which % len(sets) if sets else 0, torch.cuda.current_stream().cuda_stream)
+            if not hasattr(self, "_prepared"):
+                self._prepared = {}
+            calls = self._prepared.get(key)
+            if calls is None:
+                calls = self._prepared[key] = [run.layer.prepare(x, run.spec.stride, run.spec.pad, out=y)
+                                               for run, (x, y) in zip(self.runs, bufs)]
+            for enqueue in calls:
+                enqueue()
             return
         for li, (x, y) in enumerate(bufs):
             self.forward_layer(li, x, y, True)

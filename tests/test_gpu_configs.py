@@ -1,7 +1,7 @@
 """GPU parity on the five benchmark configurations.  Small cases are compared element by
 element; at full batch size the oracle evaluates sampled output coordinates one by one
 (exact-order double sums of the same operands the GPU layer received), once with the launch
-the cost estimate picks and once with the launches bench.py times (measured choice of 8
+the cost estimate picks and once with the launches bench.py times (measured choice of 12
 candidates per layer, re-checked inside a pass over rotating buffer sets)."""
 import numpy as np
 import pytest
@@ -294,7 +294,7 @@ def _tune_as_bench_does(net):
     """The launch selection of bench.py's default run, step by step."""
     net.autotune(12)
     net.make_buffer_sets(512 << 20)
-    return net.refine_in_context(top=4)
+    return net.refine_in_context(top=12)
 
 
 @pytest.mark.parametrize("dtype,N", [("f32", 128), ("f16", 256)])
@@ -361,3 +361,48 @@ def test_config5_unify_flag_matches_plain_rows():
     assert_close(ya, ref, TOL["f32"], "sweep-ragged-full")
     plain.close()
     unified.close()
+
+
+def test_steps_replayed_from_a_hip_graph_match_eager_steps():
+    """bench.py also records its timed steps into one HIP graph.  A graph of two steps (one per buffer set;
+    some layers with their channels dealt over two workgroups, i.e. with partial sums and arrival counters
+    that every launch has to leave at zero) is replayed three times, with eager steps and synchronisations
+    in between: after every replay all outputs equal, bit for bit, those of the eager steps."""
+    import torch
+    from paper_2011_06295_amd import workloads as wl
+    work = wl.vgg16(8, "f32")
+    net = _net(work)
+    for li in (5, 8, 11):      # 256x8x8, 512x4x4, 512x2x2
+        net.runs[li].layer.set_launch([0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 2])
+    net.run_chain(wl.make_input(work))
+    for li in (5, 8, 11):
+        s = net.runs[li].spec
+        assert net.runs[li].layer.get_launch(work.N, s.H, s.W, s.stride, s.pad)["csplit"] == 2
+    eager = [r.y.clone() for r in net.runs]
+    assert net.make_buffer_sets(2 * sum(r.x.numel() * 4 + r.y.numel() * 4 for r in net.runs)) == 2
+    net.step(0)
+    net.step(1)                # every geometry has run: nothing is built or uploaded under capture
+    torch.cuda.synchronize()
+    side, graph = torch.cuda.Stream(), torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        recorded = net.prepare_steps()
+        with torch.cuda.graph(graph, stream=side):
+            recorded[0]()
+            recorded[1]()
+    torch.cuda.synchronize()
+    for replay in range(3):
+        for bufs in net.sets:
+            for _, y in bufs:
+                y.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for which, bufs in enumerate(net.sets):
+            for li, (_, y) in enumerate(bufs):
+                assert torch.equal(y, eager[li]), (replay, which, li)
+        net.step(replay)       # the program's own eager work between replays
+        torch.cuda.synchronize()
+        for li, (_, y) in enumerate(net.sets[replay % 2]):
+            assert torch.equal(y, eager[li]), ("eager", replay, li)
+    del graph
+    net.close()
