@@ -232,6 +232,7 @@ class Network:
                 for enqueue in calls:
                     enqueue()
 
+            run_set.calls = calls
             runners.append(run_set)
         return runners
 
@@ -295,13 +296,15 @@ class Network:
     def time_pass(self, dispatch: bool, steps: int = 20, warmup: int = 3) -> float:
         """us per pass over the buffer sets in rotation, every layer through its route (dispatch) or all sparse."""
         import torch
-        for i in range(warmup):
-            self.step(i, dispatch)
+        runners = None if dispatch else self.prepare_steps()
+        one = (lambda i: self.step(i, True)) if dispatch else (lambda i: runners[i % len(runners)]())
+        for i in range(max(warmup, len(runners) if runners else 0)):
+            one(i)
         torch.cuda.synchronize()
         a, z = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         a.record()
         for i in range(steps):
-            self.step(i, dispatch)
+            one(i)
         z.record()
         torch.cuda.synchronize()
         return a.elapsed_time(z) * 1e3 / steps
