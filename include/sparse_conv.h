@@ -99,10 +99,10 @@ int sparse_conv_output_shape(sparse_conv_t h, int H, int W, int stride, int pad,
  * scratch buffer of partial sums and arrival counters: two forwards of one handle and
  * geometry must then not run at the same time (different streams without ordering).
  * Limits: input and output below 2^31 elements each (SC_EUNSUPPORTED beyond).
- * Non-finite input values: an output that the definition makes +-Inf may come
- * out as NaN (the stored rows are padded to multiples of four taps by repeating
- * a row's last tap with weight zero, and 0 * Inf is NaN); finite inputs are
- * not affected, the padding terms are exact zeros.
+ * Non-finite input values count only under a stored weight, as the definition
+ * has it: an output is NaN, +Inf or -Inf exactly where the sum over its stored
+ * weights is (the zero-weight entries that fill a stored row to a multiple of
+ * four read a zeroed region of the tile, not the input).
  */
 int sparse_conv_forward(sparse_conv_t h, const void* input, void* output,
                         int N, int H, int W, int stride, int pad, void* stream);

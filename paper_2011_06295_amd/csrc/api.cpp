@@ -151,7 +151,7 @@ void fill_args(const sparse_conv_s* h, const Plan* p, const void* input, void* o
     a.Wp = p->Wp; a.Hs = p->Hs; a.Hb = p->Hb; a.CS = p->CS; a.span = p->span;
     a.nchunks = p->nchunks; a.ngroups = p->ngroups; a.ntiles = p->ntiles; a.kblocks = p->kblocks;
     a.tile_elems = p->Cc * p->CS + 1;
-    a.SL = p->SL; a.rows_mode = p->rows_mode; a.tbl_off = p->tbl_off;
+    a.SL = p->SL; a.rows_mode = p->rows_mode; a.tbl_off = p->tbl_off; a.zero_elems = p->zero_elems;
     a.SG = p->SG; a.SP = p->SP;
     a.nbuf = p->nbuf;
     a.npass = p->npass;

@@ -129,6 +129,7 @@ struct Plan {
     int SG, SP;    // slot groups and slots per group
     int rows_mode; // staging slots: 0 whole planes group by group, 1 tile rows, 2 every element of a banded tile
     int pitch;     // row pitch inside the tile: Wp, or span + S - 1 for a banded tile
+    int zero_elems;   // elements of the zero region behind the tile buffers (what zero-weight padding entries read)
     int tbl_off;   // LDS byte offset of the slot table
     int lds_bytes; // tile + slot table
     int grid;      // workgroups launched (ntiles * kblocks rounded up to the XCD count)
@@ -203,7 +204,8 @@ struct KernelArgs {
     int SG, SP;      // rows mode: 1 group of Hb*W slots; groups mode: GC image groups of H*W slots
     int rows_mode;   // slots: 0 whole planes group by group, 1 tile rows, 2 every element of a banded tile
     int pitch;       // banded tile: elements per band (span + S - 1)
-    int tbl_off;     // byte offset of the slot table in LDS (after the tile)
+    int zero_elems;  // zeroed elements behind the tile buffers
+    int tbl_off;     // byte offset of the slot table in LDS (after the tile buffers and the zero region)
     int st_dg, st_dc, st_dp; // nthreads = st_dg * (Cc * SP) + st_dc * SP + st_dp
     int nbuf;                // tile buffers in LDS: 2 when there are several chunks
     int npass;               // staging passes per chunk: ceil(SG * Cc * SP / (kStage * threads))

@@ -693,7 +693,7 @@ __global__ __launch_bounds__(1024) void tile_kernel(const KernelArgs a)
     begin_chunk(ch_first);
     // while the first loads are in flight: padding rows/columns and absent images are zeroed
     // once and stay zero for the whole kernel (staging writes real elements only)
-    for (int u = tid; u < a.nbuf * a.tile_elems; u += nthreads) tile[u] = VT::zero();
+    for (int u = tid; u < a.nbuf * a.tile_elems + a.zero_elems; u += nthreads) tile[u] = VT::zero();   // and the zero region behind them
     __syncthreads();  // zero fill complete
     deposit(0);
     for (int p = 1; p < a.npass; ++p) {

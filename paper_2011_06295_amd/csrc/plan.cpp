@@ -47,6 +47,7 @@ struct Cand {
     int V, WP, WK, KW, Cc, LP, kblocks;
     int Hb, CS, lds, SL, rows_mode, SG, nbuf, pitch;
     int J;
+    int ZE;   // elements of the zero region behind the tile buffers
 };
 
 // Output-lane tiles: the most lattice rows between the first and the last of PT consecutive outputs
@@ -320,6 +321,14 @@ int build_plan(const Csr& csr, int C, int R, int S, int elem_bytes, const Geomet
             const bool rows_mode = banded || s.Hs >= Hb || (long long)g.H * g.W * elem_bytes >= 128;
             const long long SL = banded ? CS : rows_mode ? (long long)Hst * ge * g.W : GC * g.H * g.W;
             const long long tbl = SL * 8;
+            // The zero region: one run of zeroed elements behind the tile buffers, as long as the lanes of a
+            // wavefront spread over a channel's tile elements (furthest element under a lane + 1).  The
+            // zero-weight entries that fill a row's last batch point at it, so a lane multiplies 0 by 0
+            // there and not by whatever the input holds (0 x Inf would be NaN).
+            const int wrapG = G ? ((p.F - 1) * st + S - 1) / s.Wp : 0;
+            const long long ZE = 1 + (banded ? (long long)span - 1
+                                      : G  ? ((long long)(Hb - R - wrapG) * s.Wp + (long long)(p.F - 1) * st) * G + G - 1
+                                           : (long long)s.Wp - 1 + span - 1);
             // slot offsets are 31-bit byte offsets from the first image group of a tile
             if (GC * V * C * g.H * g.W * elem_bytes >= (1ll << 31)) continue;
             if (CS >= (1ll << 24) || SL >= (1ll << 24)) continue;
@@ -336,7 +345,7 @@ int build_plan(const Csr& csr, int C, int R, int S, int elem_bytes, const Geomet
                     for (int bi = 0; bi < 5; ++bi) {
                         if ((over.lds_budget || over.Cc) && bi) break;
                         const int budget = over.lds_budget ? over.lds_budget : budgets[bi];
-                        const long long room = budget - tbl - 32;
+                        const long long room = budget - tbl - 32 - ZE * s.ub;
                         // a chunk should not exceed what the workgroup stages in one pass (kStage units a thread)
                         const long long pass_cc = std::max<long long>(1, (long long)kStage * kWave * wp * wk / SL);
                         int Cc, nbuf = 1;
@@ -352,8 +361,8 @@ int build_plan(const Csr& csr, int C, int R, int S, int elem_bytes, const Geomet
                         if (Cc < 1) continue;
                         if (!over.Cc) Cc = cdiv(C, cdiv(C, Cc));     // even chunks
                         if (Cc < C) nbuf = 2;                        // the next chunk lands while this one is consumed
-                        // tile buffer(s), each with one spare element, table
-                        const long long lds = ((long long)nbuf * ((long long)Cc * CS + 1) * s.ub + 15) / 16 * 16 + tbl;
+                        // tile buffer(s), each with one spare element, the zero region, table
+                        const long long lds = (((long long)nbuf * ((long long)Cc * CS + 1) + ZE) * s.ub + 15) / 16 * 16 + tbl;
                         if (lds > kMaxLds) continue;
                         if (G) {   // the staging patterns of output-lane tiles must stay a small table (build below)
                             int ga = (span / G) % EF, gb = EF;
@@ -373,7 +382,7 @@ int build_plan(const Csr& csr, int C, int R, int S, int elem_bytes, const Geomet
                             if (over.csplit && J != over.csplit) continue;
                             const int nch = cdiv(C, Cc);
                             if (J > 1 && (J > nch || (long long)(J - 1) * cdiv(nch, J) >= nch)) continue;   // every part needs a chunk
-                            Cand c{V, wp, wk, kw, Cc, LP, kblocks, Hb, (int)CS, (int)lds, (int)SL, banded ? 2 : rows_mode ? 1 : 0, rows_mode ? 1 : (int)GC, nbuf, pitch, J};
+                            Cand c{V, wp, wk, kw, Cc, LP, kblocks, Hb, (int)CS, (int)lds, (int)SL, banded ? 2 : rows_mode ? 1 : 0, rows_mode ? 1 : (int)GC, nbuf, pitch, J, (int)ZE};
                             double t = estimate(s, c);
                             if (t < 0) {
                                 if (!(over.WP || over.WK || over.KW || over.Cc || over.lds_budget || over.LP || over.kblocks)) continue;
@@ -468,7 +477,8 @@ int build_plan(const Csr& csr, int C, int R, int S, int elem_bytes, const Geomet
     p.rows_mode = best.rows_mode;
     p.pitch = best.pitch;
     p.nbuf = best.nbuf;
-    p.tbl_off = (p.nbuf * (p.Cc * p.CS + 1) * s.ub + 15) / 16 * 16;
+    p.zero_elems = best.ZE;
+    p.tbl_off = (int)((((long long)p.nbuf * (p.Cc * p.CS + 1) + p.zero_elems) * s.ub + 15) / 16 * 16);
     const long long grid = (ntiles * p.kblocks * p.J + 7) / 8 * 8;   // a multiple of the XCD count
     if (ntiles > INT_MAX / 2 || grid > INT_MAX - 8) return SC_EUNSUPPORTED;
     p.ntiles = (int)ntiles;
@@ -542,7 +552,7 @@ int build_plan(const Csr& csr, int C, int R, int S, int elem_bytes, const Geomet
     // go to the device as one word per entry, with the LDS offset in 16 bits: in units of 4 bytes (2 for
     // 2-byte elements, whose tile must then stay below 128 KB; otherwise the ordinary 8-byte entries are kept).
     p.off_shift = s.ub >= 4 ? 2 : 1;
-    p.compact = (csr.coded || elem_bytes == 2) && ((long long)p.Cc * p.CS * s.ub >> p.off_shift) < 65536;
+    p.compact = (csr.coded || elem_bytes == 2) && ((long long)p.nbuf * ((long long)p.Cc * p.CS + 1) * s.ub >> p.off_shift) < 65536;
     for (int kb = 0; kb < p.kblocks; ++kb)
         for (int ch = 0; ch < nchunks; ++ch) {
             const int c0 = ch * p.Cc, c1 = std::min(C, c0 + p.Cc);
@@ -570,8 +580,11 @@ int build_plan(const Csr& csr, int C, int R, int S, int elem_bytes, const Geomet
                         p.entries.push_back(last);
                     }
                     const int nb = cdiv(n, kBatch);
-                    // padding repeats the last real tap with weight zero
-                    for (int t = n; t < nb * kBatch; ++t) p.entries.push_back(Entry{0u, last.off});
+                    // padding: weight zero, in the zero region (it lies nbuf buffers behind the first buffer's
+                    // start; this chunk is multiplied out of buffer `buf` of its part's sequence)
+                    const int buf = (ch % p.cpp) & (p.nbuf - 1);
+                    const int zero_at = (int)((long long)(p.nbuf - buf) * (p.Cc * p.CS + 1) * s.ub);
+                    for (int t = n; t < nb * kBatch; ++t) p.entries.push_back(Entry{0u, zero_at});
                     sg[1 + kk] = nb;
                     if (p.entries.size() > (size_t)INT_MAX / 2) return SC_EUNSUPPORTED;
                 }
@@ -650,7 +663,7 @@ int check_plan(const Csr& csr, int C, int R, int S, int elem_bytes, const Plan& 
     if (p.threads != kWave * p.WP * p.WK || p.threads > kWave * kMaxWaves || p.lds_bytes > kMaxLds) return 1;
     if (p.nchunks != cdiv(C, p.Cc) || (p.nbuf != 1 && p.nbuf != 2) || (p.nchunks > 1 && p.nbuf != 2)) return 1;
     if ((long long)p.tbl_off + (long long)p.SL * 8 > p.lds_bytes) return 1;
-    if ((long long)p.nbuf * ((long long)p.Cc * p.CS + 1) * ub > p.tbl_off) return 1;
+    if (((long long)p.nbuf * ((long long)p.Cc * p.CS + 1) + p.zero_elems) * ub > p.tbl_off) return 1;
     if ((long long)p.grid < (long long)p.ntiles * p.kblocks * p.J || p.grid % 8 != 0) return 1;
     if (p.J < 1 || p.J > 8 || (p.J & (p.J - 1)) || p.cpp != cdiv(p.nchunks, p.J) || (long long)(p.J - 1) * p.cpp >= p.nchunks) return 1;
     if ((long long)p.ntiles * p.span < p.npos || (long long)(p.ntiles - 1) * p.span >= p.npos) return 1;
@@ -681,6 +694,7 @@ int check_plan(const Csr& csr, int C, int R, int S, int elem_bytes, const Plan& 
             if (Yb - Ya + R + wrap > p.Hb) return 1;
         }
     }
+    if (p.zero_elems < lane_reach + 1) return 1;   // the zero region covers every lane of a wavefront
     size_t pos = 0, real = 0;
     for (int kb = 0; kb < p.kblocks; ++kb)
         for (int ch = 0; ch < p.nchunks; ++ch) {
@@ -702,7 +716,6 @@ int check_plan(const Csr& csr, int C, int R, int S, int elem_bytes, const Plan& 
                     const int n = (int)(hi - lo);
                     if (nb != cdiv(n, kBatch)) return 4;                  // batches of the row in this chunk
                     if (pos + (size_t)nb * kBatch + kBatch > p.entries.size()) return 4;
-                    int last_off = 0;
                     for (int t = 0; t < nb * kBatch; ++t) {
                         const Entry& e = p.entries[pos + t];
                         if (t < n) {
@@ -714,9 +727,9 @@ int check_plan(const Csr& csr, int C, int R, int S, int elem_bytes, const Plan& 
                             const long long elem = (long long)(c - c0) * p.CS + ((long long)r * p.pitch + sx) * ge;
                             if (e.wbits != wb || (long long)e.off != elem * ub) return 5;   // weight and tap
                             if (elem + lane_reach >= (long long)(c1 - c0) * p.CS) return 6;  // inside the chunk's tile
-                            last_off = e.off;
-                        } else if (e.wbits != 0u || e.off != last_off) {
-                            return 5;                                     // padding: weight zero, a tap already read
+                        } else if (e.wbits != 0u ||
+                                   (long long)e.off != (long long)(p.nbuf - ((ch % p.cpp) & (p.nbuf - 1))) * ((long long)p.Cc * p.CS + 1) * ub) {
+                            return 5;                                     // padding: weight zero, in the zero region
                         }
                     }
                     pos += (size_t)nb * kBatch;

@@ -393,3 +393,42 @@ def test_config1_single_layer():
     w, m = wl.make_weights(1, 1, spec), wl.make_mask(1, 1, spec)
     x = wl.make_input(work)
     check(w, m, x, spec.stride, spec.pad, "f32", what="config1")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+def test_non_finite_inputs_are_weighted_as_the_definition_says(dtype):
+    """Inputs holding +Inf, -Inf and NaN: an output is NaN, +Inf or -Inf exactly where the oracle's is (a
+    non-finite element counts only under a stored weight: the zero-weight entries that fill a row's last
+    batch read a plane of zeros, not the input), and the finite outputs stay within tolerance.  Lattice
+    lanes, output lanes and channels dealt over two workgroups."""
+    torch = _torch()
+    from paper_2011_06295_amd import binding as B
+    rng = np.random.default_rng(4242)
+    cases = [(9, 24, 20, 3, 3, 12, 12, 1, 1, []),
+             (37, 48, 40, 3, 3, 4, 4, 1, 1, [4, 0, 0, 0, 0, 0, 1, 0, 0, 5, 1]),
+             (37, 96, 40, 3, 3, 2, 2, 1, 1, [4, 0, 0, 0, 24, 0, 0, 0, 0, 1, 2]),
+             (5, 30, 17, 1, 1, 9, 9, 1, 0, []),
+             (6, 16, 33, 5, 3, 11, 14, 2, 2, [])]
+    for ci, (N, C, K, R, S, H, W, st, p, launch) in enumerate(cases):
+        w, m, x = rand_layer(rng, N, C, K, R, S, H, W, density=0.15)
+        flat = x.reshape(-1)
+        where = rng.choice(flat.size, size=12, replace=False)
+        flat[where[:5]] = np.inf
+        flat[where[5:10]] = -np.inf
+        flat[where[10:]] = np.nan
+        layer = B.SparseConv(w, m, dtype=dtype)
+        layer.set_launch(launch)
+        print(f"non-finite {dtype} case {ci}: {layer.get_launch(N, H, W, st, p)}", flush=True)
+        xt = torch.from_numpy(x).cuda()
+        xt = (xt.half() if dtype == "f16" else xt).contiguous()
+        with np.errstate(invalid="ignore", over="ignore"):
+            ref = oracle_ref(w, m, x, st, p, dtype)
+        y = layer.forward(xt, st, p)
+        torch.cuda.synchronize()
+        got = y.float().cpu().numpy().astype(np.float64)
+        assert np.isnan(ref).any() or np.isinf(ref).any()
+        assert np.array_equal(np.isnan(got), np.isnan(ref)), f"case {ci}: NaN where the oracle has none (or the reverse)"
+        assert np.array_equal(np.isposinf(got), np.isposinf(ref)) and np.array_equal(np.isneginf(got), np.isneginf(ref)), f"case {ci}"
+        fin = np.isfinite(ref)
+        assert_close(got[fin], ref[fin], TOL[dtype], f"non-finite-{dtype}-case{ci}")
+        layer.close()
