@@ -432,3 +432,39 @@ def test_non_finite_inputs_are_weighted_as_the_definition_says(dtype):
         fin = np.isfinite(ref)
         assert_close(got[fin], ref[fin], TOL[dtype], f"non-finite-{dtype}-case{ci}")
         layer.close()
+
+
+@pytest.mark.parametrize("H,J", [(2, 8), (4, 4), (8, 2)])
+def test_channel_parts_over_many_launches_with_alternating_inputs(H, J):
+    """The partial sums of a launch live in a buffer the next launch overwrites.  400 launches of a
+    512 -> 512 layer whose channels are dealt over J workgroups, on two inputs in turn: a part that read
+    sums left by the launch before (the other input's), or sums not yet written, would show as a
+    difference from that input's first result, which is checked against the oracle."""
+    torch = _torch()
+    from paper_2011_06295_amd import binding as B
+    rng = np.random.default_rng(500 + H)
+    N, C, K = 128, 512, 512
+    w = rng.standard_normal((K, C, 3, 3)).astype(np.float32)
+    m = (rng.random((K, C, 3, 3)) < 0.08).astype(np.uint8)
+    layer = B.SparseConv(w, m, dtype="f32")
+    layer.set_launch([0, 0, 0, 0, 0, 0, 0, 0, 0, 0, J])
+    info = layer.get_launch(N, H, H, 1, 1)
+    print(f"many launches {H}x{H} J={J}: {info}", flush=True)
+    assert info["csplit"] == J
+    xs = [torch.from_numpy(rng.standard_normal((N, C, H, H)).astype(np.float32)).cuda() for _ in range(2)]
+    first = []
+    for x in xs:
+        y = layer.forward(x, 1, 1)
+        torch.cuda.synchronize()
+        sub = np.arange(0, N, 16)
+        ref = oracle_ref(w, m, x[::16].cpu().numpy(), 1, 1, "f32")
+        assert_close(y[::16].float().cpu().numpy(), ref, TOL["f32"], f"many-{H}-{J}")
+        first.append(y.clone())
+    outs = [torch.empty_like(first[0]) for _ in range(4)]
+    for rep in range(100):
+        for i in range(4):
+            layer.forward(xs[i & 1], 1, 1, out=outs[i])
+        torch.cuda.synchronize()
+        for i in range(4):
+            assert torch.equal(outs[i], first[i & 1]), (rep, i)
+    layer.close()
