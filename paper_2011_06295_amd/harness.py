@@ -187,6 +187,15 @@ class Network:
                     t += e0.elapsed_time(e1)
             return t / passes
 
+        # short passes are timed more often: about 3 ms of timed passes per candidate, 8 to 64 passes
+        t0, t1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        self.step(0)
+        t0.record()
+        self.step(0)
+        t1.record()
+        torch.cuda.synchronize()
+        steps = max(steps, min(64, int(3.0 / max(t0.elapsed_time(t1), 1e-3))))
+
         for li, run in enumerate(self.runs):
             d = run.layer.get_launch(*geom(run))
             tuned = [d["V"], d["WP"], d["WK"], d["KW"], d["Cc"], 0, d["LP"], d["kblocks"], d["store"], d["lanes"], d["csplit"]]
