@@ -21,6 +21,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 from paper_2011_06295_amd.roofs import (HBM_PEAK, LDS_PEAK, VALU_PEAK_FMA, MEASURED_LDS_B_PER_CLK_PER_CU,  # noqa: E402
+                                        MEASURED_TRAFFIC_BYTES_PER_LAUNCH,
                                         MEASURED_COPY_BYTES_PER_S, CUS, CLOCK_HZ, PROFILE as ROOF_PROFILE)
 
 # what the default run reports beside the headline (configs 2, 4, 5 and 1 of the benchmark list)
@@ -376,8 +377,12 @@ def run_workload(name, args, steps, warmup, brief):
     roofline["measured_roofs"] = {"lds_B_per_clk_per_CU": MEASURED_LDS_B_PER_CLK_PER_CU,
                                   "copy_bytes_per_s": MEASURED_COPY_BYTES_PER_S, "source": ROOF_PROFILE}
     # HBM-side bytes per launch come from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (profiles/); a bench run
-    # does not measure them
-    roofline["traffic"] = None
+    # does not count them, it quotes the profile of the same workload in its default configuration
+    measured = MEASURED_TRAFFIC_BYTES_PER_LAUNCH.get(name) if not (args.launch or args.unify or args.codebook) else None
+    roofline["traffic"] = measured[0] if measured else None
+    if measured:
+        roofline["traffic_source"] = measured[1]
+        roofline["traffic_over_algorithmic"] = measured[0] / (sums["hbm_bytes"] / nl)
     roofline["kernel"] = "sc::tile_kernel"
     roofline["avg_launch_us"] = avg_launch_s * 1e6
     roofline["launches_per_step"] = nl

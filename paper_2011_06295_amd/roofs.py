@@ -17,3 +17,11 @@ VALU_PEAK_FMA_PACKED = 2 * VALU_PEAK_FMA
 MEASURED_LDS_B_PER_CLK_PER_CU = 229.4          # ds_read_b128, 64 consecutive elements per wavefront, 16 wavefronts per CU
 MEASURED_COPY_BYTES_PER_S = 4.62e12            # read + write bytes of a 1 GiB copy
 PROFILE = "profiles/roof_probes.md"
+
+# HBM-side bytes per launch of sc::tile_kernel (scaled FETCH_SIZE + WRITE_SIZE, mean over the launches of a step),
+# from the rocprofv3 --pmc runs kept under profiles/ (each names the commit it was taken at).  A bench run does
+# not count bytes; it reports these for the workloads they were measured on, in their default configuration.
+MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {
+    "vgg16_f32": (35.9e6, "profiles/tile_kernel_vgg16_f32_n128_hbm_traffic.md"),
+    "vgg16_f16": (40.5e6, "profiles/tile_kernel_vgg16_f16_n256_hbm_traffic.md"),
+}
