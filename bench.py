@@ -75,15 +75,27 @@ def oracle_leg(net, work, budget_s=12.0, npts=2000, time_it=True):
         x = r.x.float().cpu().numpy()
         y = r.y.float().cpu().numpy()
         rng = np.random.default_rng(4242 + li)
+        pool = 2 if getattr(r, "fused_pool", False) else 1      # fused store: sampled windows instead of sampled elements
         pts = np.stack([rng.integers(0, x.shape[0], npts), rng.integers(0, s.K, npts),
-                        rng.integers(0, s.E, npts), rng.integers(0, s.F, npts)], 1).astype(np.int32)
+                        rng.integers(0, s.E // pool, npts), rng.integers(0, s.F // pool, npts)], 1).astype(np.int32)
         rowptr, colidx, values = oracle.csr_encode(w, m)
         if net.unified:
             rowptr, colidx, values = r.layer.csr()
             values = values if work.dtype != "f16" else values.view(np.float16).astype(np.float32)
         if work.dtype == "f16":
             values, x = oracle.round_through_f16(values), oracle.round_through_f16(x)
-        ref = oracle.sparse_conv_points((rowptr, colidx, values), x, s.K, s.R, s.S, s.stride, s.pad, pts)
+        if pool == 2:
+            ref = None
+            for di in (0, 1):
+                for dj in (0, 1):
+                    q = pts.copy()
+                    q[:, 2], q[:, 3] = 2 * pts[:, 2] + di, 2 * pts[:, 3] + dj
+                    v = oracle.sparse_conv_points((rowptr, colidx, values), x, s.K, s.R, s.S, s.stride, s.pad, q)
+                    ref = v if ref is None else np.maximum(ref, v)
+        else:
+            ref = oracle.sparse_conv_points((rowptr, colidx, values), x, s.K, s.R, s.S, s.stride, s.pad, pts)
+        if getattr(r, "fused_relu", False):
+            ref = np.maximum(ref, 0.0)
         got = y[pts[:, 0], pts[:, 1], pts[:, 2], pts[:, 3]].astype(np.float64)
         scale = float(np.abs(ref).max()) or 1.0
         worst = max(worst, float(np.abs(got - ref).max()) / scale)
@@ -163,6 +175,9 @@ def main():
     ap.add_argument("--refine", type=int, default=1,
                     help="1: after the measured launch choice, time each layer's choice, the cost estimate's first choice "
                          "and both kinds of output store inside a pass and keep the fastest (0: skip)")
+    ap.add_argument("--fused", action="store_true",
+                    help="the ReLU and the 2 x 2 maximum that follow a layer in the workload are done in its store step "
+                         "(the pooled layers then write a quarter of the output)")
     ap.add_argument("--graph", type=int, default=1,
                     help="1: also record the K timed steps into one HIP graph and report its replay per step (0: skip)")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
@@ -180,7 +195,7 @@ def main():
         print(json.dumps(probe_roofs()))
         return
     out = run_workload(args.workload, args, args.steps, args.warmup, brief=False)
-    if args.configs and args.workload == "vgg16_f32" and not args.launch and not args.unify and not args.codebook:
+    if args.configs and args.workload == "vgg16_f32" and not args.launch and not args.unify and not args.codebook and not args.fused:
         # the other benchmark configurations, each tuned and timed by the same protocol (fewer steps, no
         # per-layer table, no CPU timing; the sampled comparison with the oracle stays)
         out["configs"] = []
@@ -245,7 +260,7 @@ def run_workload(name, args, steps, warmup, brief):
     from paper_2011_06295_amd import harness, workloads as wl
 
     work, layer_ids = make_workload(name)
-    net = harness.Network(work, unify=args.unify, layer_ids=layer_ids, codebook=args.codebook)
+    net = harness.Network(work, unify=args.unify, layer_ids=layer_ids, codebook=args.codebook, fuse=args.fused)
     if args.launch:
         for r in net.runs:
             r.layer.set_launch([int(v) for v in args.launch.split(",")])
@@ -378,7 +393,7 @@ def run_workload(name, args, steps, warmup, brief):
                                   "copy_bytes_per_s": MEASURED_COPY_BYTES_PER_S, "source": ROOF_PROFILE}
     # HBM-side bytes per launch come from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (profiles/); a bench run
     # does not count them, it quotes the profile of the same workload in its default configuration
-    measured = MEASURED_TRAFFIC_BYTES_PER_LAUNCH.get(name) if not (args.launch or args.unify or args.codebook) else None
+    measured = MEASURED_TRAFFIC_BYTES_PER_LAUNCH.get(name) if not (args.launch or args.unify or args.codebook or args.fused) else None
     roofline["traffic"] = measured[0] if measured else None
     if measured:
         roofline["traffic_source"] = measured[1]
@@ -398,7 +413,8 @@ def run_workload(name, args, steps, warmup, brief):
         "cache_hot_ms_per_step": hot_wall * 1e3 / steps, "buffer_sets": nsets,
         "graph_ms_per_step": graph_ms, "event_gap_us": round(event_gap * 1e6, 2),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": work.dtype, "data": "synthetic" + (", cluster-quantised weights (4-bit numbers, 16 centroids)" if args.codebook else ""),
+        "dtype": work.dtype, "data": "synthetic" + (", cluster-quantised weights (4-bit numbers, 16 centroids)" if args.codebook else "") +
+                (", ReLU and 2x2 maximum in the store step" if args.fused else ""),
         "config": {"workload": f"{work.name}, batch {N}, {nl} sparse conv layer(s), conv only, inputs resident in HBM, {nsets} buffer set(s) in rotation",
                    "layers": nl, "batch": N, "total_macs": total_macs,
                    "launch": ((f"override {args.launch}; " if args.launch else "") +

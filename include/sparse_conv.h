@@ -47,8 +47,9 @@ enum { SC_F32 = 0, SC_F16 = 1 };
  * the fullest row, so all output channels have one unified count. */
 enum { SC_FLAG_UNIFY_NNZ = 1u };
 
-/* Epilogue flag: apply ReLU to the stored value (sparse_conv_set_epilogue). */
-enum { SC_EPILOGUE_RELU = 1u };
+/* Epilogue flags (sparse_conv_set_epilogue): apply ReLU to the stored value; store the maximum over
+ * 2 x 2 windows (stride 2) of the map instead of the map. */
+enum { SC_EPILOGUE_RELU = 1u, SC_EPILOGUE_MAXPOOL2 = 2u };
 
 /*
  * sparse_conv_create - build the CSR form of one pruned layer (section 7).
@@ -247,9 +248,20 @@ int sparse_conv_rank_launches(sparse_conv_t h, int N, int H, int W, int stride, 
  *   bias   HOST, fp32 [K], added to every output element of channel k before
  *          anything else; NULL = no bias.  Copied by the call (one synchronous
  *          device allocation and copy).
- *   flags  0 or SC_EPILOGUE_RELU: out = max(sum + bias, 0).
- * For SC_F16 the fp32 value is rounded to binary16 once, after bias and ReLU.
- * Applies to every later forward of this handle.
+ *   flags  0, or any of
+ *          SC_EPILOGUE_RELU: out = max(sum + bias, 0);
+ *          SC_EPILOGUE_MAXPOOL2: the pooling step that follows the activation in section 3's
+ *          layer sequence, done in the store: the output is [N][K][E/2][F/2], element (i, j)
+ *          the largest of the four values (2i..2i+1, 2j..2j+1) after bias and ReLU.  Needs even
+ *          E and F and a plan with lanes as output elements whose tiles hold whole pairs of
+ *          output rows (the planner then offers only such; SC_EUNSUPPORTED from the calls that
+ *          plan a geometry if there is none: lattice lanes forced, stride above 1, or an F that
+ *          is not a power of two, since a tile is a power of two of outputs).
+ *          sparse_conv_output_shape then reports E/2 and F/2.  A window that holds a NaN gives
+ *          an unspecified one of its values.
+ * For SC_F16 the fp32 value is rounded to binary16 once, after bias, ReLU and maximum.
+ * Applies to every later forward of this handle; changing SC_EPILOGUE_MAXPOOL2 discards the
+ * handle's plans and measured launch choices.
  */
 int sparse_conv_set_epilogue(sparse_conv_t h, const float* bias, unsigned flags);
 

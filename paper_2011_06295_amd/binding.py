@@ -18,6 +18,7 @@ SC_STATIC_SCRATCH_BYTES = 16 << 20
 SC_F32, SC_F16 = 0, 1
 SC_FLAG_UNIFY_NNZ = 1
 SC_EPILOGUE_RELU = 1
+SC_EPILOGUE_MAXPOOL2 = 2
 
 # SPARSECONV_LIBRARY names another build of the same library (e.g. an instrumented one)
 LIB_PATH = os.environ.get("SPARSECONV_LIBRARY") or os.path.join(
@@ -178,7 +179,7 @@ def sparse_conv_set_launch(handle: int, params: Sequence[int]) -> None:
 
 
 def sparse_conv_set_epilogue(handle: int, bias: Optional[np.ndarray], flags: int = 0) -> None:
-    """bias: HOST fp32 [K] or None; flags: 0 or SC_EPILOGUE_RELU."""
+    """bias: HOST fp32 [K] or None; flags: 0 or any of SC_EPILOGUE_RELU, SC_EPILOGUE_MAXPOOL2."""
     b = None if bias is None else np.ascontiguousarray(bias, dtype=np.float32)
     ptr = None if b is None else b.ctypes.data_as(C.c_void_p)
     _check(_lib.sparse_conv_set_epilogue(handle, ptr, C.c_uint(flags)), "sparse_conv_set_epilogue", handle)
@@ -277,8 +278,9 @@ class SparseConv:
     def set_launch(self, params: Sequence[int]):
         sparse_conv_set_launch(self.handle, params)
 
-    def set_epilogue(self, bias: Optional[np.ndarray] = None, relu: bool = False):
-        sparse_conv_set_epilogue(self.handle, bias, SC_EPILOGUE_RELU if relu else 0)
+    def set_epilogue(self, bias: Optional[np.ndarray] = None, relu: bool = False, maxpool: bool = False):
+        sparse_conv_set_epilogue(self.handle, bias, (SC_EPILOGUE_RELU if relu else 0) | (SC_EPILOGUE_MAXPOOL2 if maxpool else 0))
+        self._shapes = {}    # the output shape of a geometry depends on the pooling flag
 
     def get_launch(self, N, H, W, stride=1, pad=0):
         return sparse_conv_get_launch(self.handle, N, H, W, stride, pad)

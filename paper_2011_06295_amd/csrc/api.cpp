@@ -53,7 +53,8 @@ int get_plan(sparse_conv_s* h, const Geometry& g, Plan** out)
         if (!p) return SC_ENOMEM;
         // a measured choice was made within the override in force (a new override discards it)
         auto tuned = h->tuned.find(g);
-        const Launch& use = tuned != h->tuned.end() ? tuned->second : h->over;
+        Launch use = tuned != h->tuned.end() ? tuned->second : h->over;
+        use.pool = (h->epilogue & SC_EPILOGUE_MAXPOOL2) ? 1 : 0;
         int rc = build_plan(h->csr, h->C, h->R, h->S, h->dtype == SC_F16 ? 2 : 4, g, use, *p);
         if (rc != SC_OK) return rc;
         static std::atomic<unsigned long long> next_id{1};
@@ -68,7 +69,8 @@ int get_plan(sparse_conv_s* h, const Geometry& g, Plan** out)
 bool buffers_overlap(const sparse_conv_s* h, const void* input, const void* output, int N, int H, int W, int stride, int pad)
 {
     const size_t b = h->dtype == SC_F16 ? 2 : 4;
-    const size_t E = (size_t)((H + 2 * pad - h->R) / stride + 1), F = (size_t)((W + 2 * pad - h->S) / stride + 1);
+    size_t E = (size_t)((H + 2 * pad - h->R) / stride + 1), F = (size_t)((W + 2 * pad - h->S) / stride + 1);
+    if (h->epilogue & SC_EPILOGUE_MAXPOOL2) E /= 2, F /= 2;
     const uintptr_t i0 = reinterpret_cast<uintptr_t>(input), o0 = reinterpret_cast<uintptr_t>(output);
     const uintptr_t i1 = i0 + (size_t)N * h->C * H * W * b, o1 = o0 + (size_t)N * h->K * E * F * b;
     return i0 < o1 && o0 < i1;
@@ -144,6 +146,8 @@ void fill_args(const sparse_conv_s* h, const Plan* p, const void* input, void* o
     a.compact = p->compact ? 1 : 0;
     a.off_shift = p->off_shift;
     a.relu = (h->epilogue & SC_EPILOGUE_RELU) ? 1 : 0;
+    a.pool = p->pool;
+    a.pool_rows = std::max(1, std::min(p->KW, p->lds_bytes / std::max(1, p->threads * p->V * 4)));
     a.nt_store = p->store == 2 ? 1 : 0;
     a.N = N; a.C = h->C; a.H = H; a.W = W; a.K = h->K; a.E = p->E; a.F = p->F;
     a.stride = stride; a.pad = pad;
@@ -382,6 +386,11 @@ int sparse_conv_output_shape(sparse_conv_t h, int H, int W, int stride, int pad,
     if (!sc::geometry_ok(h, H, W, stride, pad)) return SC_EINVAL;
     *E = (H + 2 * pad - h->R) / stride + 1;
     *F = (W + 2 * pad - h->S) / stride + 1;
+    if (h->epilogue & SC_EPILOGUE_MAXPOOL2) {
+        if ((*E | *F) & 1) return SC_EUNSUPPORTED;
+        *E /= 2;
+        *F /= 2;
+    }
     return SC_OK;
 }
 
@@ -428,7 +437,7 @@ int sparse_conv_set_launch(sparse_conv_t h, const int* params, int nparams)
 
 int sparse_conv_set_epilogue(sparse_conv_t h, const float* bias, unsigned flags)
 {
-    if (!h || (flags & ~static_cast<unsigned>(SC_EPILOGUE_RELU))) return SC_EINVAL;
+    if (!h || (flags & ~static_cast<unsigned>(SC_EPILOGUE_RELU | SC_EPILOGUE_MAXPOOL2))) return SC_EINVAL;
     float* d = nullptr;
     if (bias) {
         const int rc = sc::bind_device(h);
@@ -443,6 +452,10 @@ int sparse_conv_set_epilogue(sparse_conv_t h, const float* bias, unsigned flags)
     }
     if (h->d_bias) (void)hipFree(h->d_bias);
     h->d_bias = d;
+    if ((h->epilogue ^ flags) & SC_EPILOGUE_MAXPOOL2) {   // other tiles: plans and measured choices start afresh
+        h->plans.clear();
+        h->tuned.clear();
+    }
     h->epilogue = flags;
     return SC_OK;
 }
@@ -510,7 +523,9 @@ int sparse_conv_autotune(sparse_conv_t h, const void* input, void* output,
     try {
         std::vector<std::pair<double, sc::Launch>> ranked;
         sc::Plan scratch;
-        int rc = sc::build_plan(h->csr, h->C, h->R, h->S, h->dtype == SC_F16 ? 2 : 4, g, h->over, scratch, &ranked);
+        sc::Launch within = h->over;   // the override in force, and what the epilogue asks of the tiles
+        within.pool = (h->epilogue & SC_EPILOGUE_MAXPOOL2) ? 1 : 0;
+        int rc = sc::build_plan(h->csr, h->C, h->R, h->S, h->dtype == SC_F16 ? 2 : 4, g, within, scratch, &ranked);
         if (rc != SC_OK) return rc;
         const size_t want = max_candidates > 0 ? (size_t)max_candidates : 8;
         if (ranked.size() > want) ranked.resize(want);
@@ -602,8 +617,10 @@ int sparse_conv_rank_launches(sparse_conv_t h, int N, int H, int W, int stride, 
     try {
         std::vector<std::pair<double, sc::Launch>> ranked;
         sc::Plan scratch;
+        sc::Launch within = h->over;
+        within.pool = (h->epilogue & SC_EPILOGUE_MAXPOOL2) ? 1 : 0;
         int rc = sc::build_plan(h->csr, h->C, h->R, h->S, h->dtype == SC_F16 ? 2 : 4, sc::Geometry{N, H, W, stride, pad},
-                                h->over, scratch, &ranked);
+                                within, scratch, &ranked);
         if (rc != SC_OK) return rc;
         const int n = (int)std::min<size_t>(ranked.size(), (size_t)max_candidates);
         for (int i = 0; i < n; ++i) {

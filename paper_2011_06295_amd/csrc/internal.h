@@ -57,6 +57,8 @@ struct Launch {
                       // G image groups interleaved element by element (see Plan)
     int csplit = 0;   // parts the input channels of a (tile, channel block) are dealt over (1, 2, 4, 8), each part a
                       // workgroup of its own; the last one to finish adds the partial sums up
+    int pool = 0;     // not a launch parameter: set from the handle's epilogue.  1: the store step takes the maximum over
+                      // 2 x 2 windows, so a tile has to hold whole pairs of output rows (output lanes only)
 };
 
 struct Geometry {
@@ -110,7 +112,8 @@ struct Plan {
     int G;         // 0: lanes are lattice positions; else image groups interleaved per element, lanes are outputs
     int PT;        // G > 0: outputs per tile (span / G)
     int store;     // 1 ordinary output stores, 2 non-temporal
-    int E, F, st;  // output size, stride
+    int E, F, st;  // output size (of the convolution), stride
+    int pool;      // 1: 2 x 2 maximum in the store step (the stored map is E/2 x F/2)
     int Wp;        // row pitch of the padded lattice
     int Hs;        // rows per image group
     int span;      // positions per workgroup = 64 * WP
@@ -193,6 +196,8 @@ struct KernelArgs {
     const int* krow;
     const float* bias;   // [K] or null
     int relu;            // clamp the stored value at zero
+    int pool;            // 1: store the maximum over 2 x 2 windows of the (biased, clamped) sums: [N][K][E/2][F/2]
+    int pool_rows;       // pooled store: output channels per wavefront that go through LDS together (1..KW, as LDS allows)
     int nt_store;        // non-temporal output stores
     int N, C, H, W, K, E, F, stride, pad;
     int WP, WK, Cc, Wp, Hs, Hb, CS, span;

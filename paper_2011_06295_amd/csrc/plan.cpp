@@ -207,6 +207,8 @@ int build_plan(const Csr& csr, int C, int R, int S, int elem_bytes, const Geomet
     p.E = (g.H + 2 * pad - R) / st + 1;
     p.F = (g.W + 2 * pad - S) / st + 1;
     p.st = st;
+    p.pool = over.pool ? 1 : 0;
+    if (over.pool && ((p.E | p.F) & 1)) return SC_EUNSUPPORTED;   // windows of 2 x 2 need an even map
 
     if (over.lds_budget > kMaxLds) return SC_EINVAL;
     if (over.KW && !pow2_in(over.KW, 1, 16)) return SC_EINVAL;
@@ -238,7 +240,7 @@ int build_plan(const Csr& csr, int C, int R, int S, int elem_bytes, const Geomet
         // 32 / G outputs of one row (unit stride) times G groups.  Tried: the smallest such G and twice it
         // (larger G: more images and fewer rows of the map in a tile).
         int modes[8], nmodes = 0;
-        if (over.lanes <= 1) modes[nmodes++] = 0;
+        if (over.lanes <= 1 && !over.pool) modes[nmodes++] = 0;
         if (over.lanes > 1) {
             modes[nmodes++] = over.lanes - 1;
         } else if (over.lanes == 0 && V * elem_bytes == 16) {
@@ -295,6 +297,8 @@ int build_plan(const Csr& csr, int C, int R, int S, int elem_bytes, const Geomet
             if (G && LP != 1) continue;            // output lanes: one output per lane
             const int wp = over.WP ? over.WP : WP;
             const int span = kWave * wp * LP;
+            // 2 x 2 maximum in the store step: a tile holds whole pairs of output rows
+            if (over.pool && (!G || (span / G) % (2 * p.F) != 0)) continue;
             const int ge = G ? G : 1;
             int Hb;
             if (G) {
@@ -362,7 +366,9 @@ int build_plan(const Csr& csr, int C, int R, int S, int elem_bytes, const Geomet
                         if (!over.Cc) Cc = cdiv(C, cdiv(C, Cc));     // even chunks
                         if (Cc < C) nbuf = 2;                        // the next chunk lands while this one is consumed
                         // tile buffer(s), each with one spare element, the zero region, table
-                        const long long lds = (((long long)nbuf * ((long long)Cc * CS + 1) + ZE) * s.ub + 15) / 16 * 16 + tbl;
+                        long long lds = (((long long)nbuf * ((long long)Cc * CS + 1) + ZE) * s.ub + 15) / 16 * 16 + tbl;
+                        // (the pooled store stages one sum per thread and image in LDS)
+                        if (over.pool) lds = std::max<long long>(lds, (long long)kWave * wp * wk * V * 4);
                         if (lds > kMaxLds) continue;
                         if (G) {   // the staging patterns of output-lane tiles must stay a small table (build below)
                             int ga = (span / G) % EF, gb = EF;

@@ -32,8 +32,11 @@ class Network:
     """Handles of all layers of a workload plus their resident activations."""
 
     def __init__(self, work: wl.Workload, unify: bool = False, layer_ids: Optional[List[int]] = None,
-                 codebook: bool = False):
+                 codebook: bool = False, fuse: bool = False):
+        """fuse: the ReLU and the 2 x 2 maximum that follow a layer in the workload are done in that layer's
+        store step (where the library can plan it; elsewhere they stay torch ops between the layers)."""
         self.work = work
+        self.fuse = fuse
         self.layer_ids = layer_ids
         self.unified = unify
         self.runs: List[LayerRun] = []
@@ -50,6 +53,15 @@ class Network:
                 layer = B.SparseConv(w, m, dtype=work.dtype, unify=unify)
             rowptr = layer.csr()[0]
             self.runs.append(LayerRun(spec, layer, int(rowptr[-1])))
+            self.runs[-1].fused_relu = self.runs[-1].fused_pool = False
+            if fuse and (spec.relu_after or spec.pool_after):
+                layer.set_epilogue(None, relu=spec.relu_after, maxpool=spec.pool_after)
+                try:
+                    layer.get_launch(work.N, spec.H, spec.W, spec.stride, spec.pad)
+                    self.runs[-1].fused_pool = spec.pool_after
+                except B.SparseConvError:       # no tiles of whole row pairs for this map: pooling stays outside
+                    layer.set_epilogue(None, relu=spec.relu_after, maxpool=False)
+                self.runs[-1].fused_relu = spec.relu_after
             self.host_weights.append((w, m))
         # per layer: "sparse" (this library) or "dense" (the platform's dense convolution on the masked weights);
         # filled by compare_with_dense or load_table, honoured by step(dispatch=True) / run_chain(dispatch=True)
@@ -62,13 +74,17 @@ class Network:
         import torch
         return torch.float16 if self.work.dtype == "f16" else torch.float32
 
-    def glue(self, spec: wl.LayerSpec, y):
+    def glue(self, spec: wl.LayerSpec, y, run=None):
+        """What the workload does between this layer and the next, less what the layer's store step did already
+        (ReLU and maximum are both monotonic, so their order does not matter)."""
         import torch.nn.functional as F
-        if spec.pool_after and spec.pool_before_relu:
+        relu = spec.relu_after and not (run is not None and run.fused_relu)
+        pool = spec.pool_after and not (run is not None and run.fused_pool)
+        if pool and spec.pool_before_relu:
             y = F.max_pool2d(y, 2)
-        if spec.relu_after:
+        if relu:
             y = F.relu(y)
-        if spec.pool_after and not spec.pool_before_relu:
+        if pool and not spec.pool_before_relu:
             y = F.max_pool2d(y, 2)
         return y.contiguous()
 
@@ -143,7 +159,7 @@ class Network:
                 x = torch.from_numpy(xi).cuda().to(self.torch_dtype()).contiguous()
             run.x = x
             run.y = self.forward_layer(li - 1, x, None, dispatch)
-            x = self.glue(run.spec, run.y)
+            x = self.glue(run.spec, run.y, None if (dispatch and self.route[li - 1] == "dense") else run)
         torch.cuda.synchronize()
         return x
 

@@ -118,8 +118,20 @@ def test_argument_validation_returns_status_codes():
     assert lib.sparse_conv_set_launch(h, lp3, 7) == B.SC_OK
     assert lib.sparse_conv_set_launch(h, None, 0) == B.SC_OK
     assert lib.sparse_conv_set_epilogue(None, None, 0) == B.SC_EINVAL
-    assert lib.sparse_conv_set_epilogue(h, None, 2) == B.SC_EINVAL                               # unknown epilogue flag
+    assert lib.sparse_conv_set_epilogue(h, None, 4) == B.SC_EINVAL                               # unknown epilogue flag
     assert lib.sparse_conv_set_epilogue(h, None, B.SC_EPILOGUE_RELU) == B.SC_OK                  # no bias: nothing to copy, needs no GPU
+    # the pooled store halves the reported output shape, refuses odd maps, and is planned on the host like any other
+    assert lib.sparse_conv_set_epilogue(h, None, B.SC_EPILOGUE_RELU | B.SC_EPILOGUE_MAXPOOL2) == B.SC_OK
+    assert lib.sparse_conv_output_shape(h, 8, 8, 1, 1, C.byref(e), C.byref(f)) == B.SC_OK and (e.value, f.value) == (4, 4)
+    assert lib.sparse_conv_output_shape(h, 7, 8, 1, 1, C.byref(e), C.byref(f)) == B.SC_EUNSUPPORTED
+    info = (C.c_int * 16)()
+    assert lib.sparse_conv_get_launch(h, 8, 8, 8, 1, 1, info) == B.SC_OK and info[13] > 1         # lanes as outputs
+    assert (64 * info[1] // (info[13] - 1)) % (2 * 8) == 0                                      # a tile holds whole pairs of rows
+    status = C.c_int(-1)
+    assert lib.sparse_conv_check_plan(h, 8, 8, 8, 1, 1, C.byref(status)) == B.SC_OK and status.value == 0
+    assert lib.sparse_conv_get_launch(h, 8, 7, 7, 1, 1, info) == B.SC_EUNSUPPORTED
+    assert lib.sparse_conv_set_epilogue(h, None, 0) == B.SC_OK
+    assert lib.sparse_conv_output_shape(h, 8, 8, 1, 1, C.byref(e), C.byref(f)) == B.SC_OK and (e.value, f.value) == (8, 8)
     assert lib.sparse_conv_autotune(None, 8, 16, 1, 4, 4, 1, 0, None, 0, None) == B.SC_EINVAL    # arguments are checked before any GPU call
     assert lib.sparse_conv_autotune(h, None, 16, 1, 4, 4, 1, 0, None, 0, None) == B.SC_EINVAL
     assert lib.sparse_conv_autotune(h, 8, 8, 1, 4, 4, 1, 0, None, 0, None) == B.SC_EINVAL         # in place
@@ -297,3 +309,24 @@ def test_ranked_launches_can_be_pinned_and_plan_consistently():
             assert [got[k] for k in ("V", "WP", "WK", "KW", "Cc", "LP", "kblocks", "store")] == c[:5] + c[6:9]
             _plan_ok(layer, *geom, f"{spec.name} {c}")
         layer.close()
+
+
+def test_every_pooled_layer_of_the_benchmark_vgg_can_pool_in_its_store_step():
+    """Host only: at the benchmark batches the planner finds tiles of whole row pairs for all five layers
+    that are followed by a 2 x 2 maximum, and the plans it makes pass the plan check."""
+    from paper_2011_06295_amd import workloads as wl
+    for dtype, N in (("f32", 128), ("f16", 256)):
+        work = wl.vgg16(N, dtype)
+        pooled = 0
+        for li, spec in enumerate(work.layers, 1):
+            if not spec.pool_after:
+                continue
+            layer = B.SparseConv(wl.make_weights(work.config, li, spec), wl.make_mask(work.config, li, spec), dtype=dtype)
+            layer.set_epilogue(None, relu=True, maxpool=True)
+            info = layer.get_launch(N, spec.H, spec.W, spec.stride, spec.pad)
+            F = layer.output_shape(spec.H, spec.W, spec.stride, spec.pad)[1] * 2
+            assert info["lanes"] > 1 and (64 * info["WP"] // (info["lanes"] - 1)) % (2 * F) == 0
+            assert layer.check_plan(N, spec.H, spec.W, spec.stride, spec.pad) == 0
+            layer.close()
+            pooled += 1
+        assert pooled == 5

@@ -468,3 +468,67 @@ def test_channel_parts_over_many_launches_with_alternating_inputs(H, J):
         for i in range(4):
             assert torch.equal(outs[i], first[i & 1]), (rep, i)
     layer.close()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+def test_maximum_over_2x2_windows_in_the_store_step(dtype):
+    """Section 3's layer sequence: convolution, bias, activation, pooling.  With SC_EPILOGUE_MAXPOOL2 the
+    store step writes the E/2 x F/2 map of window maxima: against the oracle's convolution followed by its
+    ReLU and 2 x 2 maximum, on the map sizes of the 32-pixel VGG (32 ... 2), with and without bias and ReLU,
+    with the channels dealt over several workgroups, after a measured launch choice, and back to the plain store."""
+    torch = _torch()
+    from paper_2011_06295_amd import binding as B
+    rng = np.random.default_rng(808)
+    for ci, (N, C, K, H, launch) in enumerate([(9, 12, 20, 32, []), (13, 20, 24, 16, []), (21, 24, 40, 8, []),
+                                               (37, 96, 40, 4, [0, 0, 0, 0, 24, 0, 0, 0, 0, 0, 2]),
+                                               (70, 64, 24, 2, [0, 0, 0, 0, 16, 0, 0, 0, 0, 0, 4]),
+                                               (40, 16, 33, 8, [0, 0, 0, 2, 0, 0, 0, 0, 2, 0, 0])]):
+        w, m, x = rand_layer(rng, N, C, K, 3, 3, H, H, density=0.3)
+        bias = rng.standard_normal(K).astype(np.float32)
+        conv = oracle_ref(w, m, x, 1, 1, dtype).astype(np.float32)
+        layer = B.SparseConv(w, m, dtype=dtype)
+        layer.set_launch(launch)
+        xt = torch.from_numpy(x).cuda()
+        xt = (xt.half() if dtype == "f16" else xt).contiguous()
+        for b, relu in ((None, False), (bias, True)):
+            layer.set_epilogue(b, relu, maxpool=True)
+            info = layer.get_launch(N, H, H, 1, 1)
+            print(f"pooled {dtype} case {ci} bias {b is not None}: {info}", flush=True)
+            assert info["lanes"] > 1 and layer.output_shape(H, H, 1, 1) == (H // 2, H // 2)
+            if launch and launch[10]:
+                assert info["csplit"] == launch[10]
+            full = conv + (b[None, :, None, None] if b is not None else 0.0)
+            ref = oracle.maxpool2(oracle.relu(full) if relu else full)
+            y = layer.forward(xt, 1, 1)
+            torch.cuda.synchronize()
+            assert tuple(y.shape) == (N, K, H // 2, H // 2)
+            assert_close(y.float().cpu().numpy(), ref, TOL[dtype], f"pooled-{dtype}-case{ci}-bias{b is not None}")
+        if ci == 2:
+            layer.autotune(xt, 1, 1, max_candidates=6)
+            y = layer.forward(xt, 1, 1)
+            torch.cuda.synchronize()
+            assert_close(y.float().cpu().numpy(), ref, TOL[dtype], f"pooled-tuned-{dtype}")
+        layer.set_epilogue(None, False)
+        y = layer.forward(xt, 1, 1)
+        torch.cuda.synchronize()
+        assert tuple(y.shape) == (N, K, H, H)
+        assert_close(y.float().cpu().numpy(), conv, TOL[dtype], f"unpooled-again-{dtype}-case{ci}")
+        layer.close()
+
+
+def test_pooled_store_refuses_what_it_cannot_do():
+    """Odd maps, lattice lanes and strides above 1 have no tiles of whole row pairs: SC_EUNSUPPORTED."""
+    from paper_2011_06295_amd import binding as B
+    rng = np.random.default_rng(809)
+    w, m, _ = rand_layer(rng, 1, 8, 8, 3, 3, 4, 4, density=0.5)
+    layer = B.SparseConv(w, m, dtype="f32")
+    layer.set_epilogue(None, False, maxpool=True)
+    for geom in ((4, 7, 7, 1, 1), (4, 16, 16, 2, 1), (4, 6, 6, 1, 1)):     # odd map, stride 2, rows of 6 (no tile of 64 lanes holds pairs of them)
+        with pytest.raises(B.SparseConvError) as e:
+            layer.get_launch(*geom)
+        assert e.value.code == B.SC_EUNSUPPORTED
+    layer.set_launch([0, 0, 0, 0, 0, 0, 0, 0, 0, 1, 0])      # lattice lanes
+    with pytest.raises(B.SparseConvError) as e:
+        layer.get_launch(4, 8, 8, 1, 1)
+    assert e.value.code == B.SC_EUNSUPPORTED
+    layer.close()
