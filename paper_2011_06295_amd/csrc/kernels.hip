@@ -786,22 +786,20 @@ __global__ __launch_bounds__(1024) void tile_kernel(const KernelArgs a)
     const SC_CONSTANT int* kr = as_constant(la.krow) + ((size_t)kb * la.WK + wk) * KW;
     const size_t plane = (size_t)la.E * la.F;
     // ---- pooled store (the pooling step that follows the activation in section 3's layer sequence): the
-    // workgroup's sums go through LDS, one output channel per wavefront at a time, and the lane whose output
-    // is the upper left of a 2 x 2 window takes the maximum of the four and stores it into the E/2 x F/2 map.
-    // A tile holds whole pairs of output rows (the planner's condition), so a window's other three outputs
-    // are this wavefront row's lanes G, F*G and F*G + G further on.  Bias and ReLU come before the maximum.
+    // workgroup's sums (after bias and ReLU) go through LDS, as many of a wavefront's channels at a time as
+    // it holds, and the 2 x 2 windows staged there are dealt over all threads: each takes the maximum of a
+    // window's four values and stores it into the E/2 x F/2 map.  A tile holds whole pairs of output rows
+    // (the planner's condition, which makes F and the tile powers of two), so a window's other three values
+    // lie G, F*G and F*G + G elements after its first.  Consecutive threads take consecutive windows of a row.
     if constexpr (REAL) {
         if (la.pool) {
             float* stage = reinterpret_cast<float*>(smem);
             const int elems = 64 * la.WP, G = 1 << la.logG, FG = la.F << la.logG;
-            const int u = fdiv(my_o, la.fd_EF);
-            const int rem = my_o - u * (la.E * la.F);
-            const int oi = fdiv(rem, la.fd_F), oj = rem - oi * la.F;
-            const int g = (u << la.logG) + (lane & (G - 1));
-            const bool first = my_o < la.nout && g < la.ngroups && !((oi | oj) & 1);
+            const int logF = __builtin_ctz((unsigned)la.F), logW = __builtin_ctz((unsigned)elems) - 2;   // windows per slot: elems / 4
+            const int planes = la.WK * V;                           // slots (of `elems` sums) per staged channel row
             const size_t pooled = (size_t)(la.E >> 1) * (la.F >> 1);
-            const size_t pix = (size_t)(oi >> 1) * (la.F >> 1) + (oj >> 1);
-            // pool_rows of the wavefront's KW channels go through LDS together (as many as it holds): two barriers a round
+            const int o0 = tile_id * la.PT;
+            const int* krow = la.krow + (size_t)kb * la.WK * KW;
             const int rows = la.pool_rows, row_floats = (int)nthreads * V;
             float* mine = stage + (size_t)(wk * V) * elems + wp * 64 + lane;
             __syncthreads();   // nobody reads the tile any more
@@ -818,25 +816,30 @@ __global__ __launch_bounds__(1024) void tile_kernel(const KernelArgs a)
                 }
                 if (kk + 1 - round_first < rows && kk + 1 < KW) continue;
                 __syncthreads();
-                if (first) {
-                    for (int q = round_first; q <= kk; ++q) {
-                        const int kq = kr[q];
-                        if (kq < 0) continue;
-#pragma unroll
-                        for (int v = 0; v < V; ++v) {
-                            const float* w4 = mine + (q - round_first) * row_floats + v * elems;
-                            const float a0 = w4[0], a1 = w4[G], a2 = w4[FG], a3 = w4[FG + G];
-                            const float m0 = a1 > a0 ? a1 : a0, m1 = a3 > a2 ? a3 : a2;
-                            const float r = m1 > m0 ? m1 : m0;
-                            const int n = g * V + v;
-                            if (n >= la.N) continue;
-                            T* at = &y[((size_t)n * la.K + kq) * pooled + pix];
-                            if (la.nt_store)
-                                store_nontemporal(at, (T)r);
-                            else
-                                *at = (T)r;
-                        }
-                    }
+                const int windows = ((kk + 1 - round_first) * planes) << logW;
+                for (int it = tid; it < windows; it += (int)nthreads) {
+                    const int slot = it >> logW, pe = it & ((1 << logW) - 1);
+                    const int qr = slot / planes, pl = slot - qr * planes;      // staged row, (wavefront row, image) of the slot
+                    const int wkq = pl / V, v = pl - wkq * V;
+                    const int kq = krow[wkq * KW + round_first + qr];
+                    const int gsel = pe & (G - 1), po = pe >> la.logG;           // image group, window of the tile
+                    const int jj = po & ((la.F >> 1) - 1), rp = po >> (logF - 1);
+                    const int orel = (rp << (logF + 1)) + (jj << 1);             // the window's first output, in the tile
+                    const int o = o0 + orel;
+                    const int u = fdiv(o, la.fd_EF);
+                    const int rem = o - u * (la.E * la.F);
+                    const int oi = rem >> logF, oj = rem & (la.F - 1);
+                    const int n = (((u << la.logG) + gsel) * V) + v;
+                    if (kq < 0 || o >= la.nout || n >= la.N) continue;
+                    const float* w4 = stage + (size_t)slot * elems + (orel << la.logG) + gsel;
+                    const float a0 = w4[0], a1 = w4[G], a2 = w4[FG], a3 = w4[FG + G];
+                    const float m0 = a1 > a0 ? a1 : a0, m1 = a3 > a2 ? a3 : a2;
+                    const float r = m1 > m0 ? m1 : m0;
+                    T* at = &y[((size_t)n * la.K + kq) * pooled + (size_t)(oi >> 1) * (la.F >> 1) + (oj >> 1)];
+                    if (la.nt_store)
+                        store_nontemporal(at, (T)r);
+                    else
+                        *at = (T)r;
                 }
                 __syncthreads();   // the staged sums have been read: the next round's may come
                 round_first = kk + 1;
