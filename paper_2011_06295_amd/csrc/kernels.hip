@@ -25,6 +25,14 @@
 // Channel chunks alternate between two LDS buffers: the global loads of the
 // next chunk are issued into registers during the arithmetic of the current
 // one and written to the other buffer after it (one barrier per chunk).
+//
+// Second kind of tile (REAL = true): lanes are output elements, G image groups
+// interleaved element by element, so small maps spend no lanes on padding; the
+// staging units of a thread then come from a per-plan table.  Further down:
+// the issue priority that falls with the rows done, the deep form of the
+// multiply loop (a whole batch of reads in flight), channel parts (the input
+// channels of a tile dealt over several workgroups, summed by the last to
+// finish), and the store step (bias, ReLU, optionally the 2 x 2 maximum).
 #include <hip/hip_runtime.h>
 
 #include <atomic>
