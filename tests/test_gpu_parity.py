@@ -508,6 +508,9 @@ def test_maximum_over_2x2_windows_in_the_store_step(dtype):
             y = layer.forward(xt, 1, 1)
             torch.cuda.synchronize()
             assert_close(y.float().cpu().numpy(), ref, TOL[dtype], f"pooled-tuned-{dtype}")
+        ys = layer.forward_static(xt, 1, 1)          # the entry point that allocates nothing takes the same store step
+        torch.cuda.synchronize()
+        assert torch.equal(ys, layer.forward(xt, 1, 1))
         layer.set_epilogue(None, False)
         y = layer.forward(xt, 1, 1)
         torch.cuda.synchronize()
